@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the flash-attention forward hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-others]
+
+A step is one fa_fwd call (tile schedule, QK^T, mask, online softmax, PV,
+epilogue: the whole path) over one synthetic batch already resident in HBM.
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s: 4 * head_dim * heads *
+(number of visible (query, key) pairs) per call, padded and out-of-window pairs
+counting as zero work.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 matrix peak
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+HEADLINE = "c3_8k"
+
+
+def visible_pairs(lens, left, right):
+    """Number of (query, key) pairs the mask leaves visible, summed over the batch (per head)."""
+    total = 0
+    for n in lens:
+        n = int(n)
+        if n <= 0:
+            continue
+        i = np.arange(n, dtype=np.int64)
+        lo = np.zeros(n, np.int64) if left < 0 else np.maximum(0, i - left)
+        hi = np.full(n, n - 1, np.int64) if right < 0 else np.minimum(n - 1, i + right)
+        total += int((hi - lo + 1).sum())
+    return total
+
+
+def window_lr(window):
+    return (-1, -1) if window < 0 else ((window - 1) // 2, window // 2)
+
+
+def algorithmic_work(w, lens):
+    L, R = window_lr(w.window)
+    pairs = visible_pairs(lens, L, R)
+    flops = 4.0 * w.head_dim * w.heads * pairs
+    rows = int(sum(max(0, int(n)) for n in lens))
+    nbytes = 2 * 4 * w.heads * w.head_dim * rows + 4 * w.heads * rows
+    return flops, nbytes
+
+
+def read_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split("#")[0].split()
+        if len(parts) >= 3 and parts[0] == name:
+            return float(parts[1]) + float(parts[2])
+    return None
+
+
+def gpu_time(w, lens, q, k, v, steps, warmup):
+    import torch
+    import paper_2603_12646_amd as fa
+
+    tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    qd, kd, vd = (torch.from_numpy(x).to(tdt).cuda() for x in (q, k, v))
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+    sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    fn = fa.fa_fwd if w.dtype == "fp16" else fa.fa_fwd_bf16
+
+    def step():
+        fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()          # same stream the kernels are launched on (torch's current stream)
+    for _ in range(steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = start.elapsed_time(stop)
+    del qd, kd, vd, o, lse
+    return wall_ms / steps, ev_ms / steps
+
+
+def cpu_baseline(w, lens, q, k, v, budget_s=12.0):
+    """The fp64 oracle as it stands, timed on this host on whole (batch, head) slices
+    until about budget_s seconds have been spent."""
+    from oracle.attention_oracle import attention_oracle_rows
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    L, R = window_lr(w.window)
+    done_pairs, t_used, slices = 0, 0.0, 0
+    rows_per_slice = 2048
+    for b in range(w.batch):
+        n = int(lens[b])
+        if n <= 0:
+            continue
+        for h in range(w.heads):
+            rows = np.arange(0, min(n, rows_per_slice))
+            t0 = time.perf_counter()
+            for r0 in range(0, len(rows), 256):
+                attention_oracle_rows(q, k, v, b, h, rows[r0:r0 + 256], n, w.scale, L, R)
+            t_used += time.perf_counter() - t0
+            i = rows
+            lo = np.zeros_like(i) if L < 0 else np.maximum(0, i - L)
+            hi = np.full_like(i, n - 1) if R < 0 else np.minimum(n - 1, i + R)
+            done_pairs += int((hi - lo + 1).sum())
+            slices += 1
+            if t_used >= budget_s:
+                break
+        if t_used >= budget_s:
+            break
+    flops = 4.0 * w.head_dim * done_pairs
+    return {
+        "value": flops / t_used / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"first {rows_per_slice} query rows of {slices} (batch, head) slices of {w.name}, "
+                  f"full key range, {t_used:.1f} s; algorithmic flops of those rows / time",
+        "seconds": t_used,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-others", action="store_true", help="time only the named workload")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(the path shards by (batch, head) with no exchange; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from workloads import CONFIGS, make_inputs
+    import paper_2603_12646_amd as fa
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    fa.load_library()
+    torch.cuda.set_device(0)
+
+    w = CONFIGS[args.workload]
+    lens, q, k, v = make_inputs(w)
+    flops, nbytes = algorithmic_work(w, lens)
+    wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup)
+    tflops = flops / (wall_ms * 1e-3) / 1e12
+    hbm_bound = w.window >= 0
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": nbytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": flops / (ev_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = read_traffic(w.name)
+    roof["kernel_ms"] = ev_ms
+    roof["algorithmic_flops"] = flops
+    roof["algorithmic_bytes"] = nbytes
+
+    out = {
+        "metric": "attention fwd TFLOP/s (algorithmic flops; % of MFMA peak in roofline.frac); ms per call in ms_per_step",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "max_len": w.max_len,
+                   "head_dim": w.head_dim, "seq_lens": [int(x) for x in lens][:8], "window": w.window,
+                   "scale": w.scale, "qk_gain": w.qk_gain},
+        "roofline": roof,
+    }
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, lens, q, k, v)
+    del q, k, v
+
+    if not args.no_others:
+        others = {}
+        for name, ow in CONFIGS.items():
+            if name == w.name:
+                continue
+            ol, oq, ok_, ov = make_inputs(ow)
+            of, ob = algorithmic_work(ow, ol)
+            steps = max(10, min(args.steps, 100))
+            wms, ems = gpu_time(ow, ol, oq, ok_, ov, steps, max(3, min(args.warmup, 10)))
+            others[name] = {"ms_per_call": ems, "tflops": of / (ems * 1e-3) / 1e12,
+                            "frac_mfma_peak": of / (ems * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                            "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype}
+            del oq, ok_, ov
+        out["config"]["other_workloads"] = others
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,166 @@
+/*
+ * fa.h - C boundary of the MI355X (gfx950) flash-attention forward library.
+ *
+ * One operation: for every batch b, head h and valid query row i < n_b
+ *
+ *     o[b,h,i,:] = sum_j softmax_j( scale * q[b,h,i,:].k[b,h,j,:] + mask(i,j) ) * v[b,h,j,:]
+ *     lse[b,h,i] = ln sum_j exp( scale * q.k + mask )            (natural log)
+ *
+ * evaluated tile by tile with a running maximum and sum, so the n x n score
+ * matrix never exists in memory (paper Sec. 2.2: the standard attention
+ * softmax(QK^T/sqrt(d_k))V restructured by tiling and fusion into O(n) memory,
+ * same result).  mask(i,j) is 0 for visible keys and -infinity otherwise; key j
+ * is visible to query i when
+ *     j < n_b                       key-padding mask (paper Eq. 1, read as exclusion;
+ *                                   padding is the tail of each sequence), and
+ *     i - L <= j <= i + R           for a local layer with window (L, R); global layers
+ *                                   have L = R = -1 (paper Sec. 4.1.3, "ModernBERT
+ *                                   Attention Mapping": local 63/64, global -1/-1).
+ * The arguments mirror the paper's operator contract (Sec. 4.1.3: inputs
+ * Q, K, V and a 1-D padding description, attributes scale, window_size_left,
+ * window_size_right, execution on the caller's HIP stream, run-time dispatch on
+ * head_dim).
+ *
+ * Memory and layout
+ *   q, k, v, o : DEVICE pointers, [batch, heads, max_len, head_dim] row-major
+ *                (fa_fwd / fa_fwd_bf16); 16-bit elements (IEEE half or bfloat16);
+ *                each 16-byte aligned.  fa_fwd_ex takes element strides instead.
+ *   lse        : DEVICE pointer, float32 [batch, heads, max_len], or NULL to skip.
+ *   seq_lens   : DEVICE pointer, int32 [batch], valid length n_b of each sequence,
+ *                or NULL meaning n_b = max_len for all b.  Values are clamped into
+ *                [0, max_len] by the kernel (they cannot be inspected on the host
+ *                without a synchronisation).
+ *   Rows i >= n_b (padding) and rows with no visible key: o = 0, lse = -infinity.
+ *   Values stored in padded K/V/Q rows never influence valid rows, whatever
+ *   their bit patterns.
+ *
+ * Ownership and ordering
+ *   The caller owns every buffer.  The library allocates no device memory, never
+ *   synchronises, never changes the current device.  Work is enqueued on `stream`
+ *   (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *   returns immediately.  q, k, v are read-only; o and lse must not overlap them.
+ *   Results are bitwise reproducible from run to run (no atomics).
+ *
+ * Errors
+ *   0  success (work enqueued).
+ *   <0 FA_ERR_*: an invalid argument, detected on the host before anything touches
+ *      the device; nothing was enqueued.
+ *   >0 the hipError_t reported by the launch.
+ *   No exceptions, no aborts, nothing is printed.
+ */
+#ifndef FA_H
+#define FA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FA_VERSION 100 /* major*10000 + minor*100 + patch */
+
+enum {
+  FA_OK = 0,
+  FA_ERR_NULL_POINTER = -1,  /* q, k, v or o is NULL (or params is NULL)               */
+  FA_ERR_BAD_SHAPE = -2,     /* batch, heads or max_len <= 0, or too large for a grid  */
+  FA_ERR_BAD_HEAD_DIM = -3,  /* head_dim not in the supported set {64}                 */
+  FA_ERR_BAD_SCALE = -4,     /* scale is NaN or infinite (0 and negatives are legal)   */
+  FA_ERR_BAD_WINDOW = -5,    /* window == 0 (fa_fwd); window_left/right inconsistent   */
+  FA_ERR_MISALIGNED = -6,    /* a tensor pointer is not 16-byte aligned, or a stride
+                                is not a multiple of 8 elements                        */
+  FA_ERR_BAD_DTYPE = -7,     /* dtype is not FA_DTYPE_F16 / FA_DTYPE_BF16              */
+  FA_ERR_BAD_STRUCT = -8,    /* fa_params.struct_size does not match this header       */
+  FA_ERR_BAD_TUNING = -9     /* unknown bits in fa_params.tuning                       */
+};
+
+enum { FA_DTYPE_F16 = 0, FA_DTYPE_BF16 = 1 };
+
+/*
+ * fa_fwd: fp16 attention forward (the paper's kernel is fp16, Sec. 4.1.3 "HIP Kernel
+ * and ORT Registration").
+ *
+ *   batch, heads, max_len, head_dim : tensor extents; head_dim must be 64.
+ *   scale  : multiplies q.k before the softmax (the operator's `scale` attribute;
+ *            1/sqrt(head_dim) in the paper's models).  Applied in fp32 to the
+ *            fp32-accumulated dot product.
+ *   window : < 0  global layer (every valid key visible);
+ *            W >= 1 local layer with a band of W keys: L = (W-1)/2, R = W/2
+ *            (integer division), so W = 128 is the paper's 63 / 64;
+ *            0 is rejected.
+ */
+int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+           int batch, int heads, const int32_t* seq_lens, int max_len, int head_dim,
+           float scale, int window, void* stream);
+
+/* fa_fwd_bf16: identical contract with bfloat16 q, k, v, o. */
+int fa_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse,
+                int batch, int heads, const int32_t* seq_lens, int max_len, int head_dim,
+                float scale, int window, void* stream);
+
+/*
+ * fa_fwd_ex: superset entry point.  Separate left / right window extents (the
+ * paper's window_size_left / window_size_right attributes: < 0 = unbounded on
+ * that side), explicit element strides (so [batch, len, heads, dim] or a packed
+ * QKV buffer can be passed without a transpose), and a tuning word.
+ *
+ * Strides are in ELEMENTS; the head_dim axis always has stride 1.  A stride
+ * triple that is all zero selects the dense [batch, heads, max_len, head_dim]
+ * layout.  Every stride must be a multiple of 8 elements.  lse is always dense
+ * [batch, heads, max_len].
+ */
+typedef struct fa_params {
+  uint32_t struct_size; /* = sizeof(fa_params) */
+  int32_t dtype;        /* FA_DTYPE_* */
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;
+  float* lse;              /* may be NULL */
+  const int32_t* seq_lens; /* device int32[batch], may be NULL */
+  int32_t batch, heads, max_len, head_dim;
+  float scale;
+  int32_t window_left;  /* < 0: unbounded */
+  int32_t window_right; /* < 0: unbounded */
+  int64_t q_strides[3]; /* batch, head, row */
+  int64_t k_strides[3];
+  int64_t v_strides[3];
+  int64_t o_strides[3];
+  void* stream;
+  uint32_t tuning; /* 0 = library's choice; FA_TUNE_* bits force a kernel shape
+                      (for benchmarking sweeps; results are identical up to
+                      summation order) */
+} fa_params;
+
+/* tuning word: bits 0-3 query rows per workgroup, bits 4-7 V-operand path,
+   bits 8-11 workgroup-to-tile mapping. */
+#define FA_TUNE_BM_AUTO 0x0u
+#define FA_TUNE_BM_128 0x1u  /* 4 wavefronts x 32 query rows  */
+#define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows  */
+#define FA_TUNE_V_AUTO 0x00u
+#define FA_TUNE_V_LDS_TRANSPOSE 0x10u /* ds_read_b64_tr_b16 operand loads */
+#define FA_TUNE_V_SCALAR 0x20u        /* 16-bit LDS reads (slow reference path) */
+#define FA_TUNE_MAP_AUTO 0x000u
+#define FA_TUNE_MAP_LINEAR 0x100u     /* workgroup id = tile id */
+#define FA_TUNE_MAP_XCD 0x200u        /* tiles of one head kept on one XCD's L2 */
+
+int fa_fwd_ex(const fa_params* params);
+
+/*
+ * Device scratch the library needs for a call of this shape, in bytes.  The
+ * forward keeps all partial state in registers and LDS, so this is 0 for every
+ * shape: the working set is the caller's O(n) tensors only.
+ */
+size_t fa_workspace_bytes(int batch, int heads, int max_len, int head_dim);
+
+/* Static, NUL-terminated description of a return code (FA_ERR_* or 0).  Positive
+   codes map to a generic "HIP runtime error" string. */
+const char* fa_strerror(int code);
+
+/* FA_VERSION the library was built with. */
+int fa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA_H */

@@ -1,0 +1,155 @@
+// Host side of the C boundary declared in include/fa.h: argument validation,
+// mapping of the public arguments to the kernel argument block, kernel-shape
+// choice.  Nothing here touches device memory; validation failures return before
+// any HIP call.
+#include <cmath>
+#include <cfloat>
+#include <cstdint>
+#include <cstring>
+
+#include "fa.h"
+#include "fa_args.h"
+
+namespace {
+
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kTauLog2 = 8.0f;  // p = exp2(s*c - m*c) is allowed to reach 2^8 before m is refreshed
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool all_zero(const int64_t s[3]) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
+
+void dense_strides(int64_t out[3], int heads, int max_len, int head_dim) {
+  out[2] = head_dim;
+  out[1] = (int64_t)max_len * head_dim;
+  out[0] = (int64_t)heads * max_len * head_dim;
+}
+
+int resolve_strides(const int64_t in[3], int64_t out[3], int heads, int max_len, int head_dim) {
+  if (all_zero(in)) {
+    dense_strides(out, heads, max_len, head_dim);
+    return FA_OK;
+  }
+  for (int i = 0; i < 3; ++i) {
+    if (in[i] % 8 != 0) return FA_ERR_MISALIGNED;
+    out[i] = in[i];
+  }
+  if (in[2] < head_dim) return FA_ERR_BAD_SHAPE;  // rows may not overlap
+  return FA_OK;
+}
+
+int choose_bm(const fa_params& p) {
+  // Query rows per workgroup.  128 keeps more workgroups in flight (short
+  // sequences, local windows); see the tuning notes for measured crossovers.
+  (void)p;
+  return 128;
+}
+
+}  // namespace
+
+extern "C" int fa_fwd_ex(const fa_params* p) {
+  if (!p) return FA_ERR_NULL_POINTER;
+  if (p->struct_size != sizeof(fa_params)) return FA_ERR_BAD_STRUCT;
+  if (p->dtype != FA_DTYPE_F16 && p->dtype != FA_DTYPE_BF16) return FA_ERR_BAD_DTYPE;
+  if (!p->q || !p->k || !p->v || !p->o) return FA_ERR_NULL_POINTER;
+  if (p->batch <= 0 || p->heads <= 0 || p->max_len <= 0) return FA_ERR_BAD_SHAPE;
+  if (p->head_dim != 64) return FA_ERR_BAD_HEAD_DIM;
+  if (!std::isfinite(p->scale)) return FA_ERR_BAD_SCALE;
+  if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->o))
+    return FA_ERR_MISALIGNED;
+  if (p->lse && (reinterpret_cast<uintptr_t>(p->lse) & 3u)) return FA_ERR_MISALIGNED;
+  if (p->tuning & ~0x333u) return FA_ERR_BAD_TUNING;
+  const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
+  if (t_bm > FA_TUNE_BM_256 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
+    return FA_ERR_BAD_TUNING;
+
+  FaKernelArgs a;
+  std::memset(&a, 0, sizeof(a));
+  int rc;
+  if ((rc = resolve_strides(p->q_strides, a.qs, p->heads, p->max_len, p->head_dim))) return rc;
+  if ((rc = resolve_strides(p->k_strides, a.ks, p->heads, p->max_len, p->head_dim))) return rc;
+  if ((rc = resolve_strides(p->v_strides, a.vs, p->heads, p->max_len, p->head_dim))) return rc;
+  if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
+
+  const int bm = t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p));
+  const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
+  const int64_t total = n_qtiles * p->batch * p->heads;
+  // element count and grid must stay inside what the kernels index with
+  const long double elems = (long double)p->batch * p->heads * p->max_len * p->head_dim;
+  if (elems > 9.0e18L || total > 0x7FFFFFF0LL || p->max_len > (1 << 30)) return FA_ERR_BAD_SHAPE;
+
+  a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o; a.lse = p->lse; a.seq_lens = p->seq_lens;
+  a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len;
+  const float c = std::fabs(p->scale) * kLog2e;
+  a.c = c;
+  a.negate_q = std::signbit(p->scale) && p->scale != 0.0f ? 1 : 0;
+  float tau = c > 0.f ? kTauLog2 / c : FLT_MAX;
+  if (!(tau < FLT_MAX)) tau = FLT_MAX;
+  a.tau_raw = tau;
+  // a window reaching past the sequence on one side is the same as unbounded there
+  a.wl = p->window_left < 0 ? -1 : (p->window_left >= p->max_len ? -1 : p->window_left);
+  a.wr = p->window_right < 0 ? -1 : (p->window_right >= p->max_len ? -1 : p->window_right);
+  a.n_qtiles = (int32_t)n_qtiles;
+  a.total_tiles = (int32_t)total;
+  a.map_xcd = t_map == FA_TUNE_MAP_XCD ? 1 : 0;
+  const int v_path = t_v == FA_TUNE_V_SCALAR ? 1 : 0;
+
+  return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, p->stream)
+                                  : fa_launch_bf16(a, bm, v_path, p->stream);
+}
+
+static int fwd_simple(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                      int batch, int heads, const int32_t* seq_lens, int max_len, int head_dim,
+                      float scale, int window, void* stream) {
+  if (window == 0) return FA_ERR_BAD_WINDOW;
+  fa_params p;
+  std::memset(&p, 0, sizeof(p));
+  p.struct_size = sizeof(p);
+  p.dtype = dtype;
+  p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse; p.seq_lens = seq_lens;
+  p.batch = batch; p.heads = heads; p.max_len = max_len; p.head_dim = head_dim;
+  p.scale = scale;
+  if (window < 0) {
+    p.window_left = p.window_right = -1;
+  } else {
+    p.window_left = (window - 1) / 2;
+    p.window_right = window / 2;
+  }
+  p.stream = stream;
+  p.tuning = 0;
+  return fa_fwd_ex(&p);
+}
+
+extern "C" int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int batch,
+                      int heads, const int32_t* seq_lens, int max_len, int head_dim, float scale,
+                      int window, void* stream) {
+  return fwd_simple(FA_DTYPE_F16, q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scale,
+                    window, stream);
+}
+
+extern "C" int fa_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse,
+                           int batch, int heads, const int32_t* seq_lens, int max_len, int head_dim,
+                           float scale, int window, void* stream) {
+  return fwd_simple(FA_DTYPE_BF16, q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scale,
+                    window, stream);
+}
+
+extern "C" size_t fa_workspace_bytes(int, int, int, int) { return 0; }
+
+extern "C" const char* fa_strerror(int code) {
+  switch (code) {
+    case FA_OK: return "success";
+    case FA_ERR_NULL_POINTER: return "q, k, v, o or params is NULL";
+    case FA_ERR_BAD_SHAPE: return "batch, heads, max_len or a stride is out of range";
+    case FA_ERR_BAD_HEAD_DIM: return "unsupported head_dim (supported: 64)";
+    case FA_ERR_BAD_SCALE: return "scale is not finite";
+    case FA_ERR_BAD_WINDOW: return "window must be negative (global) or >= 1";
+    case FA_ERR_MISALIGNED: return "pointer not 16-byte aligned or stride not a multiple of 8";
+    case FA_ERR_BAD_DTYPE: return "dtype must be FA_DTYPE_F16 or FA_DTYPE_BF16";
+    case FA_ERR_BAD_STRUCT: return "fa_params.struct_size mismatch";
+    case FA_ERR_BAD_TUNING: return "unknown tuning bits";
+    default: return code > 0 ? "HIP runtime error" : "unknown error code";
+  }
+}
+
+extern "C" int fa_version(void) { return FA_VERSION; }

@@ -1,0 +1,28 @@
+// Argument block passed by value from the host entry points to the gfx950 kernels.
+#pragma once
+#include <stdint.h>
+
+struct FaKernelArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;
+  float* lse;               // may be null
+  const int32_t* seq_lens;  // device, may be null
+  int32_t batch, heads, max_len;
+  int64_t qs[3], ks[3], vs[3], os[3];  // element strides: batch, head, row
+  float c;          // |scale| * log2(e): scores are handled in the log2 domain
+  int32_t negate_q; // scale < 0: q's sign bits are flipped on load, c stays positive
+  float tau_raw;    // a row's reference maximum is refreshed only when a tile's maximum
+                    // exceeds it by more than this (raw score units)
+  int32_t wl, wr;   // window extents, < 0 = unbounded (already clamped to max_len)
+  int32_t n_qtiles; // ceil(max_len / BM)
+  int32_t total_tiles;  // batch * heads * n_qtiles
+  int32_t map_xcd;  // nonzero: consecutive tiles stay on one XCD
+};
+
+// Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
+// bm: 128 or 256 query rows per workgroup; v_path: 0 = LDS transpose reads,
+// 1 = 16-bit reads.
+int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, void* stream);
+int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, void* stream);

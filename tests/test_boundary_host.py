@@ -1,0 +1,105 @@
+"""Host-only checks of the C boundary: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import math
+import pathlib
+import re
+
+import pytest
+
+import paper_2603_12646_amd as fa
+
+ROOT = pathlib.Path(__file__).resolve().parent.parent
+HEADER = (ROOT / "include" / "fa.h").read_text()
+
+
+def declared_functions():
+    body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    return sorted(set(re.findall(r"\b(fa_[a-z0-9_]+)\s*\(", body)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_functions() == ["fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_strerror",
+                                    "fa_version", "fa_workspace_bytes"]
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(fa.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_struct_size_match_header():
+    m = re.search(r"#define FA_VERSION (\d+)", HEADER)
+    assert fa.fa_version() == int(m.group(1))
+    # the binding's struct must have the size the library checks against
+    p = fa.FaParams()
+    p.struct_size = ctypes.sizeof(fa.FaParams) + 8
+    assert fa.load_library().fa_fwd_ex(ctypes.byref(p)) == -8
+
+
+def test_error_enum_values_in_header_match_strerror():
+    codes = dict((name, int(val)) for name, val in re.findall(r"(FA_ERR_[A-Z_]+) = (-\d+)", HEADER))
+    assert len(codes) == 9 and sorted(codes.values()) == list(range(-9, 0))
+    seen = set()
+    for name, code in codes.items():
+        msg = fa.fa_strerror(code)
+        assert msg and msg != "unknown error code" and msg not in seen
+        seen.add(msg)
+    assert fa.fa_strerror(0) == "success"
+    assert fa.fa_strerror(-99) == "unknown error code"
+    assert fa.fa_strerror(700) == "HIP runtime error"
+
+
+def test_workspace_is_zero_for_every_shape():
+    for shape in [(1, 12, 512, 64), (32, 12, 512, 64), (1, 12, 32768, 64), (3, 12, 16384, 64)]:
+        assert fa.fa_workspace_bytes(*shape) == 0
+
+
+P = 0x1000  # a non-null, 16-byte aligned address that is never dereferenced on these paths
+
+
+def call(fn=fa.fa_fwd, q=P, k=P, v=P, o=P, lse=P, batch=1, heads=1, seq_lens=P, max_len=8,
+         head_dim=64, scale=0.125, window=-1):
+    return fn(q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scale, window,
+              stream=0, check=False)
+
+
+@pytest.mark.parametrize("fn", [fa.fa_fwd, fa.fa_fwd_bf16])
+def test_simple_entry_points_reject_bad_arguments(fn):
+    assert call(fn, q=0) == -1 and call(fn, k=0) == -1 and call(fn, v=0) == -1 and call(fn, o=0) == -1
+    assert call(fn, batch=0) == -2 and call(fn, heads=-1) == -2 and call(fn, max_len=0) == -2
+    assert call(fn, head_dim=32) == -3 and call(fn, head_dim=128) == -3 and call(fn, head_dim=0) == -3
+    assert call(fn, scale=math.nan) == -4 and call(fn, scale=math.inf) == -4 and call(fn, scale=-math.inf) == -4
+    assert call(fn, window=0) == -5
+    assert call(fn, q=P + 2) == -6 and call(fn, o=P + 8) == -6 and call(fn, lse=P + 2) == -6
+    # too many workgroups for one grid
+    assert call(fn, batch=1 << 20, heads=1 << 10, max_len=1 << 20) == -2
+
+
+def test_ex_entry_point_rejects_bad_arguments():
+    base = dict(dtype=fa.FA_DTYPE_F16, q=P, k=P, v=P, o=P, batch=1, heads=1, max_len=8, scale=1.0,
+                stream=0, check=False)
+    assert fa.fa_fwd_ex(**{**base, "dtype": 7}) == -7
+    assert fa.fa_fwd_ex(**{**base, "tuning": 0x4000}) == -9
+    assert fa.fa_fwd_ex(**{**base, "tuning": 0x3}) == -9
+    assert fa.fa_fwd_ex(**{**base, "q_strides": (512, 64, 65)}) == -6
+    assert fa.fa_fwd_ex(**{**base, "k_strides": (512, 64, 32)}) == -2
+    assert fa.load_library().fa_fwd_ex(None) == -1
+    with pytest.raises(fa.FaError) as e:
+        fa.fa_fwd_ex(**{**base, "head_dim": 48, "check": True})
+    assert e.value.code == -3
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(fa, "_lib", None)
+    monkeypatch.setattr(fa, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        fa.fa_version()
+
+
+def test_product_package_does_not_import_the_oracle():
+    for path in (ROOT / "paper_2603_12646_amd").rglob("*"):
+        if path.suffix in (".py", ".cpp", ".hip", ".h"):
+            text = path.read_text()
+            assert "oracle" not in text.lower().replace("no cpu or pytorch fallback", ""), path

@@ -1,0 +1,230 @@
+"""GPU parity: the HIP flash-attention forward, called through the C boundary,
+against the fp64 oracle on the same seeded inputs.
+
+Tolerances (valid rows, against the unrounded fp64 oracle): fp16 max-abs <= 2e-3
+and mean-abs <= 2e-4; bf16 max-abs <= 1e-2 and mean-abs <= 1e-3; logsumexp
+within 1e-3.  Edge-case tests whose outputs can exceed 1 in magnitude (self-only
+windows, one-hot softmax) scale the error by max(1, |reference|), because a
+16-bit result cannot be closer than half an ulp of its own magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_12646_amd as fa
+from oracle.attention_oracle import attention_oracle, attention_oracle_rows, window_from_width
+from workloads import CONFIGS, draw, make_inputs
+
+from tests.gpu_util import (FA_DT, LSE_TOL, TOL, check_against, poison, run_ex, run_simple, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+TUNINGS = {
+    "auto": 0,
+    "bm128_tr": fa.FA_TUNE_BM_128 | fa.FA_TUNE_V_LDS_TRANSPOSE | fa.FA_TUNE_MAP_LINEAR,
+    "bm256_tr": fa.FA_TUNE_BM_256 | fa.FA_TUNE_V_LDS_TRANSPOSE | fa.FA_TUNE_MAP_LINEAR,
+    "bm128_scalar_xcd": fa.FA_TUNE_BM_128 | fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_XCD,
+    "bm256_scalar_xcd": fa.FA_TUNE_BM_256 | fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_XCD,
+}
+
+
+# ------------------------------------------------------------------ small shapes, full compare
+@pytest.mark.parametrize("tuning", sorted(TUNINGS))
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("left,right", [(-1, -1), (63, 64), (0, 0), (3, 3), (0, 5), (70, -1), (-1, 9), (200, 130)])
+def test_small_ragged_all_windows(dtype, left, right, tuning):
+    """Several 64-key tiles plus a ragged tail (333 = 5*64 + 13), two lengths, padding
+    in the middle of a tile, every window form."""
+    B, H, N, D = 2, 3, 333, 64
+    _, q, k, v = draw(100, B, H, N, D, dtype)
+    lens = [333, 201]
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, left, right)
+    o, lse = run_ex(q, k, v, lens, dtype, 0.125, left, right, TUNINGS[tuning])
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"{dtype} {left},{right} {tuning}")
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 640])
+def test_lengths_around_tile_edges(dtype, N):
+    B, H, D = 1, 2, 64
+    _, q, k, v = draw(200 + N, B, H, N, D, dtype)
+    for window in (-1, 128, 2):
+        L, R = window_from_width(window)
+        o_ref, lse_ref = attention_oracle(q, k, v, None, 0.125, L, R)
+        o, lse = run_simple(q, k, v, None, dtype, 0.125, window)
+        check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"N={N} w={window}")
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_seq_lens_degenerate_values(dtype):
+    """n_b = 0, negative, above max_len (clamped), 1, and exactly a tile edge."""
+    B, H, N, D = 6, 2, 192, 64
+    _, q, k, v = draw(300, B, H, N, D, dtype)
+    lens = [0, -5, 1000, 1, 128, 191]
+    for window in (-1, 128):
+        L, R = window_from_width(window)
+        o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
+        o, lse = run_simple(q, k, v, lens, dtype, 0.125, window)
+        check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"w={window}")
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_padded_rows_may_hold_anything(dtype):
+    """NaN / inf / huge values in padded Q, K, V rows leave valid rows bit-identical."""
+    B, H, N, D = 2, 2, 300, 64
+    _, q, k, v = draw(301, B, H, N, D, dtype)
+    lens = [170, 255]
+    for window in (-1, 128):
+        a_o, a_lse = run_simple(q, k, v, lens, dtype, 0.125, window)
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for b, n in enumerate(lens):
+            q2[b, :, n:] = np.inf
+            k2[b, :, n:] = np.nan
+            v2[b, :, n:] = np.nan
+            v2[b, :, n::2] = -np.inf
+        b_o, b_lse = run_simple(q2, k2, v2, lens, dtype, 0.125, window)
+        assert np.array_equal(a_o, b_o) and np.array_equal(a_lse, b_lse)
+        L, R = window_from_width(window)
+        o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
+        check_against(b_o, b_lse, o_ref, lse_ref, lens, dtype, label=f"poisoned w={window}")
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("scale", [0.0, -0.125, 1.0, 0.3, 8.0])
+def test_scales(dtype, scale):
+    """scale = 0 (uniform attention), negative, not a power of two, and large
+    (near one-hot softmax, running maximum far from zero)."""
+    B, H, N, D = 1, 2, 200, 64
+    _, q, k, v = draw(302, B, H, N, D, dtype)
+    lens = [187]
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, scale)
+    o, lse = run_simple(q, k, v, lens, dtype, scale)
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"scale={scale}")
+
+
+def test_increasing_scores_force_many_rescales():
+    """Keys ordered so every tile's maximum beats the previous one by a wide margin:
+    the reference maximum must be refreshed tile after tile."""
+    N, D = 512, 64
+    rng = np.random.default_rng(7)
+    q = np.zeros((1, 1, N, D), np.float32); q[..., 0] = 1.0
+    k = np.zeros((1, 1, N, D), np.float32); k[0, 0, :, 0] = np.arange(N) * 0.25
+    v = rng.standard_normal((1, 1, N, D)).astype(np.float16).astype(np.float32)
+    for dtype in ("fp16", "bf16"):
+        o_ref, lse_ref = attention_oracle(q, k, v, None, 1.0)
+        o, lse = run_simple(q, k, v, None, dtype, 1.0)
+        check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp")
+        o_ref, lse_ref = attention_oracle(q, k[:, :, ::-1].copy(), v, None, 1.0)
+        o, lse = run_simple(q, k[:, :, ::-1].copy(), v, None, dtype, 1.0)
+        check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp down")
+
+
+def test_constant_v_and_zero_q_closed_forms():
+    """Q = 0: lse = ln(#visible keys) pins the window edges on the GPU as well."""
+    N, D = 400, 64
+    _, q, k, v = draw(303, 1, 1, N, D, "fp16")
+    q0 = np.zeros_like(q)
+    o, lse = run_simple(q0, k, v, [390], "fp16", 0.125, 128)
+    count = np.exp(lse[0, 0, :390])
+    expect = np.array([min(389, i + 64) - max(0, i - 63) + 1 for i in range(390)], float)
+    assert np.allclose(count, expect, rtol=1e-5)
+    vc = np.full_like(v, 0.75)
+    o, _ = run_simple(q, k, vc, [390], "fp16", 0.125, -1)
+    assert np.allclose(o[0, 0, :390], 0.75, atol=1e-3)
+
+
+def test_lse_null_and_other_stream_and_determinism():
+    B, H, N, D = 2, 2, 260, 64
+    _, q, k, v = draw(304, B, H, N, D, "fp16")
+    lens = [260, 100]
+    o1, lse1 = run_simple(q, k, v, lens, "fp16", 0.125, -1)
+    o2, none = run_simple(q, k, v, lens, "fp16", 0.125, -1, want_lse=False)
+    assert none is None and np.array_equal(o1, o2)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        o3, lse3 = run_simple(q, k, v, lens, "fp16", 0.125, -1, stream=s)
+    assert np.array_equal(o1, o3) and np.array_equal(lse1, lse3)
+    for _ in range(3):
+        o4, lse4 = run_simple(q, k, v, lens, "fp16", 0.125, -1)
+        assert np.array_equal(o1, o4) and np.array_equal(lse1, lse4)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_strided_inputs_bshd_and_packed_qkv(dtype):
+    """[batch, len, 3, heads, dim] packed QKV read in place, output written as
+    [batch, len, heads, dim]."""
+    B, H, N, D = 2, 3, 150, 64
+    _, q, k, v = draw(305, B, H, N, D, dtype)
+    lens = [150, 99]
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, 10, 20)
+    packed = np.stack([q, k, v], axis=0).transpose(1, 3, 0, 2, 4).copy()  # B, N, 3, H, D
+    dev = to_dev(packed, dtype)
+    o = poison((B, N, H, D), dtype)
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    sl = torch.tensor(lens, dtype=torch.int32).cuda()
+    st = (N * 3 * H * D, D, 3 * H * D)
+    fa.fa_fwd_ex(dtype=FA_DT[dtype], q=dev[:, :, 0].data_ptr(), k=dev[:, :, 1].data_ptr(),
+                 v=dev[:, :, 2].data_ptr(), o=o, lse=lse, seq_lens=sl, batch=B, heads=H, max_len=N,
+                 scale=0.125, window_left=10, window_right=20, q_strides=st, k_strides=st,
+                 v_strides=st, o_strides=(N * H * D, D, H * D))
+    torch.cuda.synchronize()
+    o_np = o.double().cpu().numpy().transpose(0, 2, 1, 3)
+    check_against(o_np, lse.double().cpu().numpy(), o_ref, lse_ref, lens, dtype, relative=True, label="strided")
+
+
+def test_valid_call_returns_zero_and_bad_call_leaves_output_untouched():
+    B, H, N, D = 1, 1, 64, 64
+    _, q, k, v = draw(306, B, H, N, D, "fp16")
+    qd, kd, vd = to_dev(q, "fp16"), to_dev(k, "fp16"), to_dev(v, "fp16")
+    o = poison((B, H, N, D), "fp16")
+    assert fa.fa_fwd(qd, kd, vd, o, None, B, H, None, N, D, 0.125, -1, check=False) == 0
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
+    o2 = poison((B, H, N, D), "fp16")
+    assert fa.fa_fwd(qd, kd, vd, o2, None, B, H, None, N, 32, 0.125, -1, check=False) == -3
+    assert fa.fa_fwd(qd, kd, vd, o2, None, B, H, None, N, D, 0.125, 0, check=False) == -5
+    torch.cuda.synchronize()
+    assert torch.isnan(o2).all()
+
+
+# ------------------------------------------------------------------ the five named workloads
+@pytest.mark.parametrize("name", ["c1_512", "c2_batch32"])
+def test_named_small_configs_full_compare(name):
+    w = CONFIGS[name]
+    lens, q, k, v = make_inputs(w)
+    L, R = window_from_width(w.window)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, w.scale, L, R)
+    o, lse = run_simple(q, k, v, lens, w.dtype, w.scale, w.window)
+    mx, mean = check_against(o, lse, o_ref, lse_ref, lens, w.dtype, label=name)
+    print(f"{name}: max-abs {mx:.3e} mean-abs {mean:.3e}")
+
+
+def sample_rows(n, rng, count):
+    edge = set(range(min(130, n))) | set(range(max(0, n - 130), n))
+    rest = rng.choice(n, size=min(count, n), replace=False).tolist()
+    return np.array(sorted(edge | set(rest)), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["c3_8k", "c4_16k_x3", "c5a_32k_global", "c5b_32k_local"])
+def test_named_large_configs_sampled_rows(name):
+    """Full-size launch, as bench.py times it; the oracle recomputes sampled query
+    rows (the first and last 130 valid rows of every (batch, head) plus random ones)
+    one by one against the full key range.  Padded rows are checked exhaustively."""
+    w = CONFIGS[name]
+    lens, q, k, v = make_inputs(w)
+    L, R = window_from_width(w.window)
+    o, lse = run_simple(q, k, v, lens, w.dtype, w.scale, w.window)
+    rng = np.random.default_rng(11)
+    tol = TOL[w.dtype]
+    worst, total, count = 0.0, 0.0, 0
+    for b in range(w.batch):
+        n = int(lens[b])
+        assert np.all(o[b, :, n:] == 0) and np.all(np.isneginf(lse[b, :, n:]))
+        for h in range(w.heads):
+            rows = sample_rows(n, rng, 384)
+            o_ref, lse_ref = attention_oracle_rows(q, k, v, b, h, rows, n, w.scale, L, R)
+            d = np.abs(o[b, h, rows] - o_ref)
+            assert np.all(np.isfinite(o[b, h, rows]))
+            worst = max(worst, float(d.max())); total += float(d.sum()); count += d.size
+            assert np.abs(lse[b, h, rows] - lse_ref).max() <= LSE_TOL, (name, b, h)
+    print(f"{name}: max-abs {worst:.3e} mean-abs {total / count:.3e} over {count} sampled outputs")
+    assert worst <= tol["max_abs"] and total / count <= tol["mean_abs"]
