@@ -264,8 +264,11 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_kernel(const FaKernelArgs a) 
             tmax = fmaxf(tmax, sv);
           }
           tmax = fmaxf(tmax, xor32(tmax));
-          if (__any((tmax - m_ref[qb]) > a.tau_raw)) {
-            const float m_new = fmaxf(m_ref[qb], tmax);
+          // A lane refreshes its reference only on its own row's evidence, so what a
+          // row computes never depends on which other rows share its wavefront.
+          const bool refresh = (tmax - m_ref[qb]) > a.tau_raw;
+          if (__any(refresh)) {
+            const float m_new = refresh ? tmax : m_ref[qb];
             const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * a.c;
             const float alpha = __builtin_amdgcn_exp2f(mc[qb] - mc_new);
             m_ref[qb] = m_new;

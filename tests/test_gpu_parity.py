@@ -12,7 +12,7 @@ import torch
 
 import paper_2603_12646_amd as fa
 from oracle.attention_oracle import attention_oracle, attention_oracle_rows, window_from_width
-from workloads import CONFIGS, draw, make_inputs
+from workloads import CONFIGS, draw, make_inputs, round_to_storage
 
 from tests.gpu_util import (FA_DT, LSE_TOL, TOL, check_against, poison, run_ex, run_simple, to_dev)
 
@@ -108,8 +108,10 @@ def test_increasing_scores_force_many_rescales():
     rng = np.random.default_rng(7)
     q = np.zeros((1, 1, N, D), np.float32); q[..., 0] = 1.0
     k = np.zeros((1, 1, N, D), np.float32); k[0, 0, :, 0] = np.arange(N) * 0.25
-    v = rng.standard_normal((1, 1, N, D)).astype(np.float16).astype(np.float32)
+    v0 = rng.standard_normal((1, 1, N, D)).astype(np.float32)
+    k0 = k
     for dtype in ("fp16", "bf16"):
+        k, v = round_to_storage(k0, dtype), round_to_storage(v0, dtype)
         o_ref, lse_ref = attention_oracle(q, k, v, None, 1.0)
         o, lse = run_simple(q, k, v, None, dtype, 1.0)
         check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp")
