@@ -67,7 +67,7 @@ def read_traffic(name):
     return None
 
 
-def gpu_time(w, lens, q, k, v, steps, warmup):
+def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0):
     import torch
     import paper_2603_12646_amd as fa
 
@@ -78,8 +78,16 @@ def gpu_time(w, lens, q, k, v, steps, warmup):
     sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
     fn = fa.fa_fwd if w.dtype == "fp16" else fa.fa_fwd_bf16
 
+    L, R = window_lr(w.window)
+    dt = fa.FA_DTYPE_F16 if w.dtype == "fp16" else fa.FA_DTYPE_BF16
+
     def step():
-        fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
+        if tuning:   # sweeps only: force a kernel shape through the superset entry point
+            fa.fa_fwd_ex(dtype=dt, q=qd, k=kd, v=vd, o=o, lse=lse, seq_lens=sl, batch=w.batch,
+                         heads=w.heads, max_len=w.max_len, head_dim=w.head_dim, scale=w.scale,
+                         window_left=L, window_right=R, tuning=tuning)
+        else:
+            fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
 
     for _ in range(warmup):
         step()
@@ -145,6 +153,8 @@ def main():
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-others", action="store_true", help="time only the named workload")
+    ap.add_argument("--tuning", type=lambda x: int(x, 0), default=0,
+                    help="FA_TUNE_* bits forwarded to fa_fwd_ex (sweeps); 0 = library's choice")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -164,7 +174,7 @@ def main():
     w = CONFIGS[args.workload]
     lens, q, k, v = make_inputs(w)
     flops, nbytes = algorithmic_work(w, lens)
-    wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup)
+    wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup, args.tuning)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     hbm_bound = w.window >= 0
     if hbm_bound:
@@ -186,7 +196,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "max_len": w.max_len,
                    "head_dim": w.head_dim, "seq_lens": [int(x) for x in lens][:8], "window": w.window,
-                   "scale": w.scale, "qk_gain": w.qk_gain},
+                   "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning},
         "roofline": roof,
     }
 
@@ -202,7 +212,7 @@ def main():
             ol, oq, ok_, ov = make_inputs(ow)
             of, ob = algorithmic_work(ow, ol)
             steps = max(10, min(args.steps, 100))
-            wms, ems = gpu_time(ow, ol, oq, ok_, ov, steps, max(3, min(args.warmup, 10)))
+            wms, ems = gpu_time(ow, ol, oq, ok_, ov, steps, max(3, min(args.warmup, 10)), args.tuning)
             others[name] = {"ms_per_call": ems, "tflops": of / (ems * 1e-3) / 1e12,
                             "frac_mfma_peak": of / (ems * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                             "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype}

@@ -2,7 +2,7 @@
 // fp32 accumulation, key-padding mask by sequence length, optional local window.
 //
 // The operation is softmax(scale * Q K^T + mask) V per (batch, head), evaluated
-// one key tile at a time with a running row maximum and row sum so that no
+// one key block at a time with a running row maximum and row sum so that no
 // n x n matrix is ever formed (paper Sec. 2.2; operator attributes scale,
 // window_size_left/right and the 1-D padding mask from Sec. 4.1.3 and Eq. 1).
 //
@@ -10,7 +10,7 @@
 //   * a workgroup owns BM = 4*32*NQB query rows of one (batch, head); each
 //     wavefront owns NQB blocks of 32 query rows and keeps their Q fragments,
 //     running maximum / sum and the 64-wide output accumulator in registers;
-//   * K and V are streamed through LDS in tiles of BN = 64 keys, double buffered,
+//   * K and V are streamed through LDS in tiles of 64 keys, double buffered,
 //     fetched from HBM/L2 with 16-byte loads one tile ahead of the arithmetic.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_{f16,bf16}, D = A * B + C with
@@ -29,13 +29,19 @@
 //     HBM) and is fetched with the LDS transpose read ds_read_b64_tr_b16.
 //
 // Softmax (log2 domain, c = scale*log2(e)):  p = exp2(s*c - m*c).  The reference
-// maximum m of a row is only refreshed when a tile's maximum exceeds it by more
+// maximum m of a row is only refreshed when a block's maximum exceeds it by more
 // than a threshold (2^8 in p); rescaling the accumulator is then rare, and the
 // result is unchanged because numerator and denominator share the reference.
+//
+// Two kernels:
+//   fa_fwd_global_kernel  global layers (no window).  Full 64-key tiles run in a
+//       software pipeline over 32-key blocks: while the vector ALU turns block u's
+//       scores into probabilities, the matrix cores compute block u+1's scores and
+//       accumulate block u-1's P.V.  The ragged last tile takes the masked path.
+//   fa_fwd_masked_kernel  local-window layers (and one-sided windows): every tile
+//       is masked per element, and key blocks outside a wavefront's band are skipped.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#include <type_traits>
 
 #include "fa_args.h"
 
@@ -54,8 +60,11 @@ constexpr int kD = 64;        // head_dim
 constexpr int kBN = 64;       // keys per LDS tile
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-constexpr int kSK = kD + 8;   // LDS row stride of the K tile, in 16-bit elements
-constexpr int kSV = kD + 8;   // LDS row stride of the V tile
+// LDS row strides in 16-bit elements.  K is read with 16-byte accesses by 32 rows at
+// once (row stride 36 dwords puts 8 consecutive rows on disjoint banks); V is read by
+// the transpose load, 4 rows x 32 bytes per 16 lanes (row stride 40 dwords).
+constexpr int kSK = kD + 8;
+constexpr int kSV = kD + 16;
 constexpr float kLn2 = 0.693147180559945309f;
 
 struct F16 {
@@ -66,6 +75,10 @@ struct F16 {
   static __device__ __forceinline__ uint32_t pack2(float a, float b) {  // round to nearest even
     half2v h = __builtin_convertvector((floatx2){a, b}, half2v);
     return __builtin_bit_cast(uint32_t, h);
+  }
+  // acc + lo + hi of a packed pair, accumulated in fp32
+  static __device__ __forceinline__ float sum2(uint32_t pk, float acc) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, pk), (half2v){1, 1}, acc, false);
   }
 };
 
@@ -78,22 +91,180 @@ struct BF16 {
     bf2v h = __builtin_convertvector((floatx2){a, b}, bf2v);
     return __builtin_bit_cast(uint32_t, h);
   }
+  static __device__ __forceinline__ float sum2(uint32_t pk, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2v, pk),
+                                           (bf2v){(__bf16)1.0f, (__bf16)1.0f}, acc, false);
+  }
 };
 
-__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+// Exchange between the two lanes (l, l ^ 32) that hold the same query: afterwards
+// a = x of the lower lane of the pair and b = x of the upper one, in both lanes.
+// v_permlane32_swap exchanges lanes 32..63 of its first register with lanes 0..31 of
+// its second.  Written as asm because the compiler folds the builtin's two results
+// into one when both inputs are the same value; the s_nops cover the VALU-write ->
+// permlane-read hazards the compiler cannot see inside an asm block.
+__device__ __forceinline__ void swap_halves(float x, float& a, float& b) {
+  a = x;
+  asm("s_nop 1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "=&v"(b));
+}
+__device__ __forceinline__ float max_xor32(float x) {
+  float a, b;
+  swap_halves(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  float a, b;
+  swap_halves(x, a, b);
+  return a + b;
+}
 
 template <class T>
 __device__ __forceinline__ typename T::v8 as_v8(uint4 u) {
   return __builtin_bit_cast(typename T::v8, u);
 }
 
-template <class T, int NQB, bool V_TR>
-__global__ __launch_bounds__(kThreads) void fa_fwd_kernel(const FaKernelArgs a) {
-  constexpr int BM = kWaves * 32 * NQB;
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kBN * kSK];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kBN * kSV];
+// A operand of S^T = K Q^T for one k-step: K[row l%32][16*ks + 8*(l/32) .. +7]
+template <class T>
+__device__ __forceinline__ typename T::v8 load_k_frag(const uint16_t* kblk, int l32, int hh, int ks) {
+  return as_v8<T>(*(const uint4*)&kblk[l32 * kSK + ks * 16 + hh * 8]);
+}
 
-  // ---- which tile ------------------------------------------------------------
+// A operand of O^T = V^T P^T: column d = 32*db + l%32 of V, summation slots
+// (hh, e) = keys 16*ks2 + (e < 4 ? 4*hh + e : 8 + 4*hh + e - 4) of the 32-key block.
+// Within 16 lanes, lane p fetches 4 consecutive d of key row p/4; the transpose
+// read hands lane i the 4 keys of column i.
+template <class T>
+__device__ __forceinline__ typename T::v8 load_vt_frag(const uint16_t* vblk, int lane, int ks2, int db) {
+  const int hh = lane >> 5, p16 = lane & 15;
+  const int row = ks2 * 16 + 4 * hh + (p16 >> 2);
+  const int col = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
+  typedef __attribute__((address_space(3))) shortx4 lds_s4;
+  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * kSV + col]);
+  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * kSV + col]);
+  shortx8 x;
+  x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
+  x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
+  return __builtin_bit_cast(typename T::v8, x);
+}
+
+// Same operand through plain 16-bit LDS reads (slow; kept as an independent path).
+template <class T>
+__device__ __forceinline__ typename T::v8 load_vt_frag_scalar(const uint16_t* vblk, int lane, int ks2, int db) {
+  const int hh = lane >> 5, l32 = lane & 31;
+  shortx8 x;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int row = ks2 * 16 + (e < 4 ? 4 * hh + e : 8 + 4 * hh + e - 4);
+    x[e] = (short)vblk[row * kSV + db * 32 + l32];
+  }
+  return __builtin_bit_cast(typename T::v8, x);
+}
+
+template <int NQB>
+struct RowState {
+  floatx16 oacc[NQB][2];  // O^T: [qb][d block], rows d = 32*db + 8*(r/4) + 4*hh + r%4
+  float m_ref[NQB];       // reference maximum (raw score units), -inf before the first key
+  float mc[NQB];          // m_ref * c, 0 while m_ref = -inf
+  float lsum[NQB];        // this lane's share of the row sum
+};
+
+// Refresh the reference of rows whose block maximum ran away from it.  Each lane
+// decides on its own row's evidence only, so a row's arithmetic never depends on
+// which other rows share its wavefront.
+template <int NQB>
+__device__ __forceinline__ void rescale_rows(RowState<NQB>& st, int qb, bool refresh, float tmax, float c) {
+  const float m_new = refresh ? tmax : st.m_ref[qb];
+  const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * c;
+  // nothing has been accumulated while the old reference is -inf: keep 0 * alpha out of
+  // reach of an infinite alpha
+  const float alpha = (st.m_ref[qb] == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.mc[qb] - mc_new);
+  st.m_ref[qb] = m_new;
+  st.mc[qb] = mc_new;
+  st.lsum[qb] *= alpha;
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha;
+}
+
+// One 32-key block, scores to accumulator, with per-element masking if MASKED.
+// kblk / vblk: LDS rows of the block; kb0: its first key index; [jlo, jhi] per lane
+// is the visible key range of the lane's query.
+template <class T, int NQB, bool MASKED, bool V_TR>
+__device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T::v8 (&qreg)[NQB][4],
+                                             const uint16_t* kblk, const uint16_t* vblk, int kb0,
+                                             const int (&jlo)[NQB], const int (&jhi)[NQB], int lane,
+                                             float c, float tau_raw) {
+  const int l32 = lane & 31, hh = lane >> 5;
+  floatx16 sacc[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const typename T::v8 ka = load_k_frag<T>(kblk, l32, hh, ks);
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) sacc[qb] = T::mfma(ka, qreg[qb][ks], sacc[qb]);
+  }
+  uint32_t pk[NQB][8];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    uint32_t vis = 0xFFFFu;
+    if (MASKED) {
+      vis = 0;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int jg = kb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+        vis |= (jg >= jlo[qb] && jg <= jhi[qb]) ? (1u << r) : 0u;
+      }
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float sv = (!MASKED || (vis >> r & 1)) ? sacc[qb][r] : -INFINITY;
+      tmax = fmaxf(tmax, sv);
+    }
+    tmax = max_xor32(tmax);
+    const bool refresh = (tmax - st.m_ref[qb]) > tau_raw;
+    if (__any(refresh)) rescale_rows<NQB>(st, qb, refresh, tmax, c);
+    const float nmc = -st.mc[qb];
+    float p[16];
+    float ls = st.lsum[qb];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], c, nmc));
+      if (MASKED) e = (vis >> r & 1) ? e : 0.f;
+      p[r] = e;
+      ls += e;
+    }
+    st.lsum[qb] = ls;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) pk[qb][r] = T::pack2(p[2 * r], p[2 * r + 1]);
+  }
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2) {
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+      const typename T::v8 va = V_TR ? load_vt_frag<T>(vblk, lane, ks2, db)
+                                     : load_vt_frag_scalar<T>(vblk, lane, ks2, db);
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const uint4 pu = make_uint4(pk[qb][ks2 * 4 + 0], pk[qb][ks2 * 4 + 1], pk[qb][ks2 * 4 + 2],
+                                    pk[qb][ks2 * 4 + 3]);
+        st.oacc[qb][db] = T::mfma(va, as_v8<T>(pu), st.oacc[qb][db]);
+      }
+    }
+  }
+}
+
+// ---- pieces shared by both kernels ----------------------------------------------------
+struct TileCoord {
+  int b, h, qt, n, q0;
+};
+
+template <int BM>
+__device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc) {
   int tile = blockIdx.x;
   if (a.map_xcd) {
     // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
@@ -101,58 +272,36 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_kernel(const FaKernelArgs a) 
     const int per = (a.total_tiles + 7) >> 3;
     tile = (tile & 7) * per + (tile >> 3);
   }
-  if (tile >= a.total_tiles) return;
-  const int qt = tile % a.n_qtiles;
+  if (tile >= a.total_tiles) return false;
+  tc.qt = tile % a.n_qtiles;
   const int bh = tile / a.n_qtiles;
-  const int h = bh % a.heads;
-  const int b = bh / a.heads;
-  const int N = a.max_len;
-
-  int n = N;
+  tc.h = bh % a.heads;
+  tc.b = bh / a.heads;
+  int n = a.max_len;
   if (a.seq_lens) {
-    n = a.seq_lens[b];
-    n = n < 0 ? 0 : (n > N ? N : n);
+    n = a.seq_lens[tc.b];
+    n = n < 0 ? 0 : (n > a.max_len ? a.max_len : n);
   }
-  const int q0 = qt * BM;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: lets key-block skips be scalar branches
-  const int l32 = lane & 31;
-  const int hh = lane >> 5;
+  tc.n = n;
+  tc.q0 = tc.qt * BM;
+  return true;
+}
 
-  const uint16_t* qp = (const uint16_t*)a.q + b * a.qs[0] + h * a.qs[1];
-  const uint16_t* kp = (const uint16_t*)a.k + b * a.ks[0] + h * a.ks[1];
-  const uint16_t* vp = (const uint16_t*)a.v + b * a.vs[0] + h * a.vs[1];
-  uint16_t* op = (uint16_t*)a.o + b * a.os[0] + h * a.os[1];
-  float* lsep = a.lse ? a.lse + ((int64_t)b * a.heads + h) * N : nullptr;
+// Workgroup entirely in the padding: o = 0, lse = -inf.
+template <int BM>
+__device__ __forceinline__ void zero_fill(const FaKernelArgs& a, const TileCoord& tc, uint16_t* op, float* lsep) {
+  const int tid = threadIdx.x, N = a.max_len;
+  const int r = tid >> 3, c16 = tid & 7;
+  for (int row = tc.q0 + r; row < tc.q0 + BM && row < N; row += 32)
+    *(uint4*)(op + row * a.os[2] + c16 * 8) = make_uint4(0, 0, 0, 0);
+  if (lsep)
+    for (int row = tc.q0 + tid; row < tc.q0 + BM && row < N; row += kThreads) lsep[row] = -INFINITY;
+}
 
-  // ---- workgroup entirely in the padding: zero-fill and leave -----------------
-  if (q0 >= n) {
-    const int r = tid >> 3, c16 = tid & 7;
-    for (int row = q0 + r; row < q0 + BM && row < N; row += 32) {
-      *(uint4*)(op + row * a.os[2] + c16 * 8) = make_uint4(0, 0, 0, 0);
-    }
-    if (lsep) {
-      for (int row = q0 + tid; row < q0 + BM && row < N; row += kThreads) lsep[row] = -INFINITY;
-    }
-    return;
-  }
-
-  // ---- key range of this workgroup ---------------------------------------------
-  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
-  int lo = 0, hi = n;
-  if (a.wl >= 0) lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
-  if (a.wr >= 0) hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
-  const int t_lo = lo / kBN;
-  const int t_hi = (hi + kBN - 1) / kBN;
-  const bool windowed = (a.wl >= 0) || (a.wr >= 0);
-
-  // ---- this wavefront's queries --------------------------------------------------
-  const int qw0 = q0 + wave * 32 * NQB;
-  const int qw_last = (qw0 + 32 * NQB < n ? qw0 + 32 * NQB : n) - 1;  // < qw0: all padding
-  const bool wave_has_rows = qw_last >= qw0;
-
-  typename T::v8 qreg[NQB][4];
+template <class T, int NQB>
+__device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp, int qw0, int lane,
+                                       typename T::v8 (&qreg)[NQB][4]) {
+  const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     int row = qw0 + qb * 32 + l32;
@@ -167,21 +316,106 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_kernel(const FaKernelArgs a) 
       qreg[qb][ks] = as_v8<T>(u);
     }
   }
+}
 
-  floatx16 oacc[NQB][2];
-  float m_ref[NQB], mc[NQB], lsum[NQB];
+template <int NQB>
+__device__ __forceinline__ void init_state(RowState<NQB>& st) {
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    m_ref[qb] = -INFINITY;
-    mc[qb] = 0.f;
-    lsum[qb] = 0.f;
+    st.m_ref[qb] = -INFINITY;
+    st.mc[qb] = 0.f;
+    st.lsum[qb] = 0.f;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
+      for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] = 0.f;
+  }
+}
+
+template <class T, int NQB>
+__device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& st, uint16_t* op, float* lsep,
+                                         int qw0, int n, int lane) {
+  const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int ig = qw0 + qb * 32 + l32;
+    const float ltot = sum_xor32(st.lsum[qb]);
+    if (ig >= N) continue;
+    const bool live = (ig < n) && (ltot > 0.f);
+    const float inv = live ? 1.0f / ltot : 0.f;
+    uint16_t* orow = op + ig * a.os[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w;
+        w.x = T::pack2(st.oacc[qb][db][4 * g + 0] * inv, st.oacc[qb][db][4 * g + 1] * inv);
+        w.y = T::pack2(st.oacc[qb][db][4 * g + 2] * inv, st.oacc[qb][db][4 * g + 3] * inv);
+        if (!live) w = make_uint2(0, 0);
+        *(uint2*)(orow + db * 32 + 8 * g + 4 * hh) = w;
+      }
+    }
+    if (lsep && hh == 0)
+      lsep[ig] = live ? (st.mc[qb] + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+  }
+}
+
+// ======================================================================================
+// Masked kernel: windows (and any tile that needs per-element masks)
+// ======================================================================================
+template <class T, int NQB, bool V_TR>
+__global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelArgs a) {
+  constexpr int BM = kWaves * 32 * NQB;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kBN * kSK];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kBN * kSV];
+
+  TileCoord tc;
+  if (!locate_tile<BM>(a, tc)) return;
+  const int N = a.max_len, n = tc.n, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  if (q0 >= n) {
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
   }
 
-  // ---- staging: thread t moves 16 bytes of rows t/8 and t/8 + 32 -------------------
+  // key range of this workgroup
+  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  int lo = 0, hi = n;
+  if (a.wl >= 0) lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
+  if (a.wr >= 0) hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
+  const int t_lo = lo / kBN;
+  const int t_hi = (hi + kBN - 1) / kBN;
+
+  // this wavefront's queries
+  const int qw0 = q0 + wave * 32 * NQB;
+  const int qw_last = (qw0 + 32 * NQB < n ? qw0 + 32 * NQB : n) - 1;  // < qw0: all padding
+  const bool wave_has_rows = qw_last >= qw0;
+
+  typename T::v8 qreg[NQB][4];
+  load_q<T, NQB>(a, qp, qw0, lane, qreg);
+  RowState<NQB> st;
+  init_state<NQB>(st);
+  int jlo[NQB], jhi[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int ig = qw0 + qb * 32 + l32;
+    jlo[qb] = 0;
+    jhi[qb] = n - 1;
+    if (a.wl >= 0 && ig - a.wl > jlo[qb]) jlo[qb] = ig - a.wl;
+    if (a.wr >= 0 && ig + a.wr < jhi[qb]) jhi[qb] = ig + a.wr;
+  }
+
+  // staging: thread t moves 16 bytes of rows t/8 and t/8 + 32
   const int st_r = tid >> 3, st_c = (tid & 7) * 8;
   uint4 kst[2], vst[2];
   auto fetch = [&](int t) {
@@ -211,162 +445,271 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_kernel(const FaKernelArgs a) 
   int buf = 0;
   for (int t = t_lo; t < t_hi; ++t) {
     if (t + 1 < t_hi) fetch(t + 1);
-
-    const int tile_j0 = t * kBN;
-    // interior tiles (every key visible to every query of the workgroup) take the
-    // instantiation without any per-element mask work
-    auto tile_compute = [&](auto masked_tag) {
-      constexpr bool masked = decltype(masked_tag)::value;
+    if (wave_has_rows) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const int kb0 = tile_j0 + kb * 32;
-        if (masked) {  // wavefront-uniform: skip key blocks no query of this wavefront sees
-          if (kb0 >= n) continue;
-          if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
-          if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
-        }
-
-        // S^T block: 32 keys x 32 queries per qb
-        floatx16 sacc[NQB];
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const uint4 ku = *(const uint4*)&lds_k[buf][(kb * 32 + l32) * kSK + ks * 16 + hh * 8];
-          const typename T::v8 ka = as_v8<T>(ku);
-#pragma unroll
-          for (int qb = 0; qb < NQB; ++qb) sacc[qb] = T::mfma(ka, qreg[qb][ks], sacc[qb]);
-        }
-
-        // online softmax; lane holds query (qb, l32) and keys kb0 + 8*(r/4) + 4*hh + r%4
-        uint32_t pk[NQB][8];
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          const int ig = qw0 + qb * 32 + l32;
-          uint32_t vis = 0xFFFFu;
-          if (masked) {
-            vis = 0;
-            int jlo = 0, jhi = n - 1;
-            if (a.wl >= 0 && ig - a.wl > jlo) jlo = ig - a.wl;
-            if (a.wr >= 0 && ig + a.wr < jhi) jhi = ig + a.wr;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int jg = kb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-              vis |= (jg >= jlo && jg <= jhi) ? (1u << r) : 0u;
-            }
-          }
-          float tmax = -INFINITY;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float sv = (!masked || (vis >> r & 1)) ? sacc[qb][r] : -INFINITY;
-            tmax = fmaxf(tmax, sv);
-          }
-          tmax = fmaxf(tmax, xor32(tmax));
-          // A lane refreshes its reference only on its own row's evidence, so what a
-          // row computes never depends on which other rows share its wavefront.
-          const bool refresh = (tmax - m_ref[qb]) > a.tau_raw;
-          if (__any(refresh)) {
-            const float m_new = refresh ? tmax : m_ref[qb];
-            const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * a.c;
-            const float alpha = __builtin_amdgcn_exp2f(mc[qb] - mc_new);
-            m_ref[qb] = m_new;
-            mc[qb] = mc_new;
-            lsum[qb] *= alpha;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-          }
-          const float nmc = -mc[qb];
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], a.c, nmc));
-            if (masked) e = (vis >> r & 1) ? e : 0.f;
-            p[r] = e;
-            lsum[qb] += e;
-          }
-#pragma unroll
-          for (int r = 0; r < 8; ++r) pk[qb][r] = T::pack2(p[2 * r], p[2 * r + 1]);
-        }
-
-        // O^T += V^T * P^T ; summation slot (hh, e) of k-step ks2 is key
-        // kb*32 + 16*ks2 + (e < 4 ? 4*hh + e : 8 + 4*hh + e - 4)
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-#pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            typename T::v8 va;
-            if (V_TR) {
-              // within 16 lanes, lane p fetches 4 consecutive d of key row p/4; the
-              // transpose hands lane i the 4 keys of column i.
-              const int p16 = lane & 15;
-              const int row = kb * 32 + ks2 * 16 + 4 * hh + (p16 >> 2);
-              const int col = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
-              typedef __attribute__((address_space(3))) shortx4 lds_s4;
-              const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (lds_s4*)&lds_v[buf][row * kSV + col]);
-              const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (lds_s4*)&lds_v[buf][(row + 8) * kSV + col]);
-              shortx8 x;
-              x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
-              x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
-              va = __builtin_bit_cast(typename T::v8, x);
-            } else {
-              shortx8 x;
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const int row = kb * 32 + ks2 * 16 + (e < 4 ? 4 * hh + e : 8 + 4 * hh + e - 4);
-                x[e] = (short)lds_v[buf][row * kSV + db * 32 + l32];
-              }
-              va = __builtin_bit_cast(typename T::v8, x);
-            }
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
-              uint4 pu = make_uint4(pk[qb][ks2 * 4 + 0], pk[qb][ks2 * 4 + 1], pk[qb][ks2 * 4 + 2],
-                                    pk[qb][ks2 * 4 + 3]);
-              oacc[qb][db] = T::mfma(va, as_v8<T>(pu), oacc[qb][db]);
-            }
-          }
-        }
+        const int kb0 = t * kBN + kb * 32;
+        // wavefront-uniform: skip key blocks no query of this wavefront sees
+        if (kb0 >= n) continue;
+        if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
+        if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
+        simple_block<T, NQB, true, V_TR>(st, qreg, &lds_k[buf][kb * 32 * kSK], &lds_v[buf][kb * 32 * kSV],
+                                         kb0, jlo, jhi, lane, a.c, a.tau_raw);
       }
-    };
-    if (wave_has_rows) {
-      if (windowed || (tile_j0 + kBN > n)) tile_compute(std::true_type{});
-      else tile_compute(std::false_type{});
     }
-
     if (t + 1 < t_hi) stash(buf ^ 1);
     __syncthreads();
     buf ^= 1;
   }
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane);
+}
 
-  // ---- epilogue -----------------------------------------------------------------------
+// ======================================================================================
+// Global kernel: software pipeline over the full tiles + masked ragged tail
+// ======================================================================================
+template <class T, int NQB>
+struct PipeRegs {
+  floatx16 s[2][NQB];               // scores of the current / next block
+  typename T::v8 p[2][NQB][2];      // packed probabilities of the previous / current block
+};
+
+template <class T, int NQB, int WAVES_PER_EU>
+__global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
+  constexpr int BM = kWaves * 32 * NQB;
+  // the two stages of each array are contiguous: the tail treats lds_v as 128 rows
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * kSK];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * kSV];
+
+  TileCoord tc;
+  if (!locate_tile<BM>(a, tc)) return;
+  const int N = a.max_len, n = tc.n, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  if (q0 >= n) {
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+
+  const int qw0 = q0 + wave * 32 * NQB;
+  const int qw_last = (qw0 + 32 * NQB < n ? qw0 + 32 * NQB : n) - 1;
+  const bool wave_has_rows = qw_last >= qw0;
+
+  typename T::v8 qreg[NQB][4];
+  load_q<T, NQB>(a, qp, qw0, lane, qreg);
+  RowState<NQB> st;
+  init_state<NQB>(st);
+
+  const int nf = n / kBN;  // full tiles: every key visible to every valid query
+  const float c = a.c, tau_raw = a.tau_raw;
+
+  // Staging for the pipeline.  Iteration t of the pipeline works on score blocks
+  // u = 2t, 2t+1 (32 keys each) but touches K of blocks u+1 and V of blocks u-1, so the
+  // LDS "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t-32, 64t+32).
+  const int st_r = tid >> 3, st_c = (tid & 7) * 8;
+  uint4 kst[2], vst[2];
+  auto fetch = [&](int t) {
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int ig = qw0 + qb * 32 + l32;
-    const float ltot = lsum[qb] + xor32(lsum[qb]);
-    if (ig >= N) continue;
-    const bool live = (ig < n) && (ltot > 0.f);
-    const float inv = live ? 1.0f / ltot : 0.f;
-    uint16_t* orow = op + ig * a.os[2];
-#pragma unroll
-    for (int db = 0; db < 2; ++db) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 w;
-        w.x = T::pack2(oacc[qb][db][4 * g + 0] * inv, oacc[qb][db][4 * g + 1] * inv);
-        w.y = T::pack2(oacc[qb][db][4 * g + 2] * inv, oacc[qb][db][4 * g + 3] * inv);
-        if (!live) w = make_uint2(0, 0);
-        *(uint2*)(orow + db * 32 + 8 * g + 4 * hh) = w;
-      }
+    for (int p = 0; p < 2; ++p) {
+      int jk = t * kBN + 32 + p * 32 + st_r;
+      int jv = t * kBN - 32 + p * 32 + st_r;
+      jk = jk < 0 ? 0 : (jk < N ? jk : N - 1);
+      jv = jv < 0 ? 0 : (jv < N ? jv : N - 1);
+      kst[p] = *(const uint4*)(kp + jk * a.ks[2] + st_c);
+      vst[p] = *(const uint4*)(vp + jv * a.vs[2] + st_c);
     }
-    if (lsep && hh == 0) {
-      lsep[ig] = live ? (mc[qb] + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      *(uint4*)&lds_k[buf * kBN * kSK + (p * 32 + st_r) * kSK + st_c] = kst[p];
+      *(uint4*)&lds_v[buf * kBN * kSV + (p * 32 + st_r) * kSV + st_c] = vst[p];
+    }
+  };
+
+  PipeRegs<T, NQB> pr;
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) pr.p[0][qb][ks2] = as_v8<T>(make_uint4(0, 0, 0, 0));
+
+  if (nf > 0) {
+    // prologue: block 0's scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
+    fetch(-1);
+    stash(1);
+    fetch(0);
+    stash(0);
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) pr.s[0][qb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const typename T::v8 ka = load_k_frag<T>(&lds_k[kBN * kSK + 32 * kSK], l32, hh, ks);
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) pr.s[0][qb] = T::mfma(ka, qreg[qb][ks], pr.s[0][qb]);
+    }
+    __syncthreads();  // stage 1 is overwritten at the end of iteration 0
+
+    // One pipeline step: probabilities of block `cur`, scores of the next block, P.V of
+    // the previous block.
+    auto step = [&](floatx16 (&s_cur)[NQB], floatx16 (&s_nxt)[NQB], typename T::v8 (&p_prev)[NQB][2],
+                    typename T::v8 (&p_cur)[NQB][2], const uint16_t* kblk, const uint16_t* vblk) {
+      // -- reference check (rare refresh)
+      float tmax[NQB];
+      bool refresh[NQB];
+      bool any = false;
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float t0 = fmaxf(s_cur[qb][0], s_cur[qb][1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[qb][r]), s_cur[qb][r + 1]);
+        tmax[qb] = max_xor32(t0);
+        refresh[qb] = (tmax[qb] - st.m_ref[qb]) > tau_raw;
+        any |= refresh[qb];
+      }
+      if (__any(any)) {
+        // bring the accumulator up to date in the old reference, then rescale it
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const typename T::v8 va = load_vt_frag<T>(vblk, lane, ks2, db);
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) st.oacc[qb][db] = T::mfma(va, p_prev[qb][ks2], st.oacc[qb][db]);
+          }
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+#pragma unroll
+          for (int ks2 = 0; ks2 < 2; ++ks2) p_prev[qb][ks2] = as_v8<T>(make_uint4(0, 0, 0, 0));
+          rescale_rows<NQB>(st, qb, refresh[qb], tmax[qb], c);
+        }
+      }
+      // -- matrix work of this step: next scores, previous P.V
+      typename T::v8 ka[4], va[2][2];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag<T>(kblk, l32, hh, ks);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) va[ks2][db] = load_vt_frag<T>(vblk, lane, ks2, db);
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_nxt[qb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) s_nxt[qb] = T::mfma(ka[ks], qreg[qb][ks], s_nxt[qb]);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb) st.oacc[qb][db] = T::mfma(va[ks2][db], p_prev[qb][ks2], st.oacc[qb][db]);
+      // -- vector work of this step: probabilities of the current block
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float nmc = -st.mc[qb];
+        uint32_t pk[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r], c, nmc));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r + 1], c, nmc));
+          pk[r] = T::pack2(e0, e1);
+        }
+        // the row sum is taken over the ROUNDED probabilities, the same numbers the
+        // matrix product uses, two per instruction
+        float l0 = st.lsum[qb], l1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; r += 2) {
+          l0 = T::sum2(pk[r], l0);
+          l1 = T::sum2(pk[r + 1], l1);
+        }
+        st.lsum[qb] = l0 + l1;
+        p_cur[qb][0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+        p_cur[qb][1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
+      }
+    };
+
+    int buf = 0;
+    for (int t = 0; t < nf; ++t) {
+      if (t + 1 < nf) fetch(t + 1);
+      if (wave_has_rows) {
+        const uint16_t* kt = &lds_k[buf * kBN * kSK];
+        const uint16_t* vt = &lds_v[buf * kBN * kSV];
+        step(pr.s[0], pr.s[1], pr.p[0], pr.p[1], kt, vt);
+        step(pr.s[1], pr.s[0], pr.p[1], pr.p[0], kt + 32 * kSK, vt + 32 * kSV);
+      }
+      if (t + 1 < nf) stash(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
     }
   }
+
+  // ---- drain + ragged tail -------------------------------------------------------------
+  // lds_v rows 0..31: V of the last full block (its P.V is still pending);
+  // lds_v rows 32..95 and lds_k rows 0..63: the partial tile [64 nf, 64 nf + 64).
+  const int tail = n - nf * kBN;
+  {
+    const int base = nf * kBN;
+    for (int i = tid; i < 96 * 8; i += kThreads) {
+      const int row = i >> 3, c8 = (i & 7) * 8;
+      const int jg = base - 32 + row;
+      const int jc = jg < 0 ? 0 : (jg < N ? jg : N - 1);
+      uint4 vv = *(const uint4*)(vp + jc * a.vs[2] + c8);
+      if (jg >= n) vv = make_uint4(0, 0, 0, 0);  // 0 * (anything stored in the padding) must be 0
+      *(uint4*)&lds_v[row * kSV + c8] = vv;
+    }
+    if (tail > 0) {
+      for (int i = tid; i < 64 * 8; i += kThreads) {
+        const int row = i >> 3, c8 = (i & 7) * 8;
+        const int jg = base + row;
+        const int jc = jg < N ? jg : N - 1;
+        *(uint4*)&lds_k[row * kSK + c8] = *(const uint4*)(kp + jc * a.ks[2] + c8);
+      }
+    }
+  }
+  __syncthreads();
+  if (wave_has_rows) {
+    if (nf > 0) {
+      // after an even number of steps the pending probabilities sit in p[0]
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const typename T::v8 va = load_vt_frag<T>(lds_v, lane, ks2, db);
+#pragma unroll
+          for (int qb = 0; qb < NQB; ++qb)
+            st.oacc[qb][db] = T::mfma(va, pr.p[0][qb][ks2], st.oacc[qb][db]);
+        }
+    }
+    if (tail > 0) {
+      int jlo[NQB], jhi[NQB];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        jlo[qb] = 0;
+        jhi[qb] = n - 1;
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const int kb0 = nf * kBN + kb * 32;
+        if (kb0 >= n) continue;
+        simple_block<T, NQB, true, true>(st, qreg, &lds_k[kb * 32 * kSK], &lds_v[(32 + kb * 32) * kSV], kb0,
+                                         jlo, jhi, lane, c, tau_raw);
+      }
+    }
+  }
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane);
 }
 
 template <class T>
@@ -375,12 +718,16 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   unsigned grid = (unsigned)a.total_tiles;
   if (a.map_xcd) grid = (unsigned)(((a.total_tiles + 7) / 8) * 8);
   hipStream_t s = (hipStream_t)stream;
-  if (bm == 256) {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
+  const bool global = a.wl < 0 && a.wr < 0;
+  if (global && v_path == 0) {
+    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 1>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
+  } else if (bm == 256) {
+    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
   } else {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_kernel<T, 1, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_kernel<T, 1, false>), dim3(grid), block, 0, s, a);
+    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 1, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 1, false>), dim3(grid), block, 0, s, a);
   }
   return (int)hipGetLastError();
 }
