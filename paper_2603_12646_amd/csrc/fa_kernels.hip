@@ -415,27 +415,26 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
     if (a.wr >= 0 && ig + a.wr < jhi[qb]) jhi[qb] = ig + a.wr;
   }
 
-  // staging: thread t moves 16 bytes of rows t/8 and t/8 + 32
+  // staging: thread t moves 16 bytes of rows t/8 and t/8 + 32 (named registers, not an
+  // array: an array captured by the lambdas ends up in scratch memory)
   const int st_r = tid >> 3, st_c = (tid & 7) * 8;
-  uint4 kst[2], vst[2];
+  uint4 kst0, kst1, vst0, vst1;
+  auto fetch_row = [&](int jg, uint4& kk, uint4& vv) {
+    const int jc = jg < N ? jg : N - 1;
+    kk = *(const uint4*)(kp + jc * a.ks[2] + st_c);
+    vv = *(const uint4*)(vp + jc * a.vs[2] + st_c);
+    // padded V rows are replaced by zeros: 0 * (whatever is stored there) must be 0
+    if (jg >= n) vv = make_uint4(0, 0, 0, 0);
+  };
   auto fetch = [&](int t) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int jg = t * kBN + p * 32 + st_r;
-      const int jc = jg < N ? jg : N - 1;
-      kst[p] = *(const uint4*)(kp + jc * a.ks[2] + st_c);
-      uint4 vv = *(const uint4*)(vp + jc * a.vs[2] + st_c);
-      // padded V rows are replaced by zeros: 0 * (whatever is stored there) must be 0
-      if (jg >= n) vv = make_uint4(0, 0, 0, 0);
-      vst[p] = vv;
-    }
+    fetch_row(t * kBN + st_r, kst0, vst0);
+    fetch_row(t * kBN + 32 + st_r, kst1, vst1);
   };
   auto stash = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      *(uint4*)&lds_k[buf][(p * 32 + st_r) * kSK + st_c] = kst[p];
-      *(uint4*)&lds_v[buf][(p * 32 + st_r) * kSV + st_c] = vst[p];
-    }
+    *(uint4*)&lds_k[buf][st_r * kSK + st_c] = kst0;
+    *(uint4*)&lds_k[buf][(32 + st_r) * kSK + st_c] = kst1;
+    *(uint4*)&lds_v[buf][st_r * kSV + st_c] = vst0;
+    *(uint4*)&lds_v[buf][(32 + st_r) * kSV + st_c] = vst1;
   };
 
   fetch(t_lo);
@@ -515,24 +514,20 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // u = 2t, 2t+1 (32 keys each) but touches K of blocks u+1 and V of blocks u-1, so the
   // LDS "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t-32, 64t+32).
   const int st_r = tid >> 3, st_c = (tid & 7) * 8;
-  uint4 kst[2], vst[2];
+  uint4 kst0, kst1, vst0, vst1;  // named registers: an array here ends up in scratch memory
+  auto clampN = [&](int j) { return j < 0 ? 0 : (j < N ? j : N - 1); };
   auto fetch = [&](int t) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      int jk = t * kBN + 32 + p * 32 + st_r;
-      int jv = t * kBN - 32 + p * 32 + st_r;
-      jk = jk < 0 ? 0 : (jk < N ? jk : N - 1);
-      jv = jv < 0 ? 0 : (jv < N ? jv : N - 1);
-      kst[p] = *(const uint4*)(kp + jk * a.ks[2] + st_c);
-      vst[p] = *(const uint4*)(vp + jv * a.vs[2] + st_c);
-    }
+    const int jk = t * kBN + 32 + st_r, jv = t * kBN - 32 + st_r;
+    kst0 = *(const uint4*)(kp + clampN(jk) * a.ks[2] + st_c);
+    kst1 = *(const uint4*)(kp + clampN(jk + 32) * a.ks[2] + st_c);
+    vst0 = *(const uint4*)(vp + clampN(jv) * a.vs[2] + st_c);
+    vst1 = *(const uint4*)(vp + clampN(jv + 32) * a.vs[2] + st_c);
   };
   auto stash = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      *(uint4*)&lds_k[buf * kBN * kSK + (p * 32 + st_r) * kSK + st_c] = kst[p];
-      *(uint4*)&lds_v[buf * kBN * kSV + (p * 32 + st_r) * kSV + st_c] = vst[p];
-    }
+    *(uint4*)&lds_k[buf * kBN * kSK + st_r * kSK + st_c] = kst0;
+    *(uint4*)&lds_k[buf * kBN * kSK + (32 + st_r) * kSK + st_c] = kst1;
+    *(uint4*)&lds_v[buf * kBN * kSV + st_r * kSV + st_c] = vst0;
+    *(uint4*)&lds_v[buf * kBN * kSV + (32 + st_r) * kSV + st_c] = vst1;
   };
 
   PipeRegs<T, NQB> pr;
@@ -596,12 +591,21 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       }
       // -- matrix work of this step: next scores, previous P.V
       typename T::v8 ka[4], va[2][2];
+#ifdef FA_X_NOLDS
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) ka[ks] = qreg[0][ks];
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < 2; ++db) va[ks2][db] = qreg[0][ks2 * 2 + db];
+#else
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag<T>(kblk, l32, hh, ks);
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
         for (int db = 0; db < 2; ++db) va[ks2][db] = load_vt_frag<T>(vblk, lane, ks2, db);
+#endif
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
@@ -623,9 +627,13 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         uint32_t pk[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
+#ifdef FA_X_NOSOFTMAX
+          pk[r] = (__builtin_bit_cast(uint32_t, s_cur[qb][2 * r]) & 0x3fff3fffu) ^ __builtin_bit_cast(uint32_t, s_cur[qb][2 * r + 1] + nmc);
+#else
           const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r], c, nmc));
           const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r + 1], c, nmc));
           pk[r] = T::pack2(e0, e1);
+#endif
         }
         // the row sum is taken over the ROUNDED probabilities, the same numbers the
         // matrix product uses, two per instruction
@@ -643,15 +651,21 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
 
     int buf = 0;
     for (int t = 0; t < nf; ++t) {
+#ifndef FA_X_NOFETCH
       if (t + 1 < nf) fetch(t + 1);
+#endif
       if (wave_has_rows) {
         const uint16_t* kt = &lds_k[buf * kBN * kSK];
         const uint16_t* vt = &lds_v[buf * kBN * kSV];
         step(pr.s[0], pr.s[1], pr.p[0], pr.p[1], kt, vt);
         step(pr.s[1], pr.s[0], pr.p[1], pr.p[0], kt + 32 * kSK, vt + 32 * kSV);
       }
+#ifndef FA_X_NOFETCH
       if (t + 1 < nf) stash(buf ^ 1);
+#endif
+#ifndef FA_X_NOBARRIER
       __syncthreads();
+#endif
       buf ^= 1;
     }
   }
