@@ -66,6 +66,9 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kSK = kD + 8;
 constexpr int kSV = kD + 16;
 constexpr float kLn2 = 0.693147180559945309f;
+// A lane's 16 probabilities of one block may sum to at most this (against the row's
+// current reference) before the reference is refreshed; far inside fp16 range.
+constexpr float kPLimit = 1024.f;
 
 struct F16 {
   typedef half8 v8;
@@ -515,13 +518,20 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // LDS "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t-32, 64t+32).
   const int st_r = tid >> 3, st_c = (tid & 7) * 8;
   uint4 kst0, kst1, vst0, vst1;  // named registers: an array here ends up in scratch memory
-  auto clampN = [&](int j) { return j < 0 ? 0 : (j < N ? j : N - 1); };
+  // Row bases are wavefront-uniform (scalar registers); each thread adds a fixed 32-bit
+  // offset, so a tile fetch costs no vector address arithmetic.  Halves whose rows
+  // would leave [0, N) are only ever the unused ends of the pipeline (V before block 0,
+  // K after the last full block): their base is clamped, never their contents used.
+  const uint32_t koff = (uint32_t)(st_r * a.ks[2] + st_c), voff = (uint32_t)(st_r * a.vs[2] + st_c);
   auto fetch = [&](int t) {
-    const int jk = t * kBN + 32 + st_r, jv = t * kBN - 32 + st_r;
-    kst0 = *(const uint4*)(kp + clampN(jk) * a.ks[2] + st_c);
-    kst1 = *(const uint4*)(kp + clampN(jk + 32) * a.ks[2] + st_c);
-    vst0 = *(const uint4*)(vp + clampN(jv) * a.vs[2] + st_c);
-    vst1 = *(const uint4*)(vp + clampN(jv + 32) * a.vs[2] + st_c);
+    const int k0r = t * kBN + 32 < 0 ? 0 : t * kBN + 32;
+    const int k1r = t * kBN + 64 > N - 32 ? N - 32 : t * kBN + 64;
+    const int v0r = t * kBN - 32 < 0 ? 0 : t * kBN - 32;
+    const int v1r = t * kBN < 0 ? 0 : t * kBN;
+    kst0 = *(const uint4*)(kp + (int64_t)k0r * a.ks[2] + koff);
+    kst1 = *(const uint4*)(kp + (int64_t)k1r * a.ks[2] + koff);
+    vst0 = *(const uint4*)(vp + (int64_t)v0r * a.vs[2] + voff);
+    vst1 = *(const uint4*)(vp + (int64_t)v1r * a.vs[2] + voff);
   };
   auto stash = [&](int buf) {
     *(uint4*)&lds_k[buf * kBN * kSK + st_r * kSK + st_c] = kst0;
@@ -556,39 +566,34 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     __syncthreads();  // stage 1 is overwritten at the end of iteration 0
 
     // One pipeline step: probabilities of block `cur`, scores of the next block, P.V of
-    // the previous block.
+    // the previous block.  The probabilities are formed against the row's current
+    // reference right away; the block's row-sum share doubles as the overflow sentinel
+    // (any p beyond kPLimit, an infinity included, pushes it over).  Only then - rarely -
+    // is the exact block maximum computed, the reference refreshed and the block redone.
+    auto softmax_block = [&](const floatx16& sv, float mcq, uint32_t (&pk)[8], float& blk) {
+      const float nmc = -mcq;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+#ifdef FA_X_NOSOFTMAX
+        pk[r] = (__builtin_bit_cast(uint32_t, sv[2 * r]) & 0x3fff3fffu) ^ __builtin_bit_cast(uint32_t, sv[2 * r + 1] + nmc);
+#else
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r], c, nmc));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r + 1], c, nmc));
+        pk[r] = T::pack2(e0, e1);
+#endif
+      }
+      // the row sum is taken over the ROUNDED probabilities, the same numbers the
+      // matrix product uses, two per instruction
+      float l0 = 0.f, l1 = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; r += 2) {
+        l0 = T::sum2(pk[r], l0);
+        l1 = T::sum2(pk[r + 1], l1);
+      }
+      blk = l0 + l1;
+    };
     auto step = [&](floatx16 (&s_cur)[NQB], floatx16 (&s_nxt)[NQB], typename T::v8 (&p_prev)[NQB][2],
                     typename T::v8 (&p_cur)[NQB][2], const uint16_t* kblk, const uint16_t* vblk) {
-      // -- reference check (rare refresh)
-      float tmax[NQB];
-      bool refresh[NQB];
-      bool any = false;
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        float t0 = fmaxf(s_cur[qb][0], s_cur[qb][1]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[qb][r]), s_cur[qb][r + 1]);
-        tmax[qb] = max_xor32(t0);
-        refresh[qb] = (tmax[qb] - st.m_ref[qb]) > tau_raw;
-        any |= refresh[qb];
-      }
-      if (__any(any)) {
-        // bring the accumulator up to date in the old reference, then rescale it
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            const typename T::v8 va = load_vt_frag<T>(vblk, lane, ks2, db);
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) st.oacc[qb][db] = T::mfma(va, p_prev[qb][ks2], st.oacc[qb][db]);
-          }
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-#pragma unroll
-          for (int ks2 = 0; ks2 < 2; ++ks2) p_prev[qb][ks2] = as_v8<T>(make_uint4(0, 0, 0, 0));
-          rescale_rows<NQB>(st, qb, refresh[qb], tmax[qb], c);
-        }
-      }
       // -- matrix work of this step: next scores, previous P.V
       typename T::v8 ka[4], va[2][2];
 #ifdef FA_X_NOLDS
@@ -621,31 +626,35 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
 #pragma unroll
           for (int qb = 0; qb < NQB; ++qb) st.oacc[qb][db] = T::mfma(va[ks2][db], p_prev[qb][ks2], st.oacc[qb][db]);
       // -- vector work of this step: probabilities of the current block
+      uint32_t pk[NQB][8];
+      float blk[NQB];
+      bool trig = false;
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
-        const float nmc = -st.mc[qb];
-        uint32_t pk[8];
+        softmax_block(s_cur[qb], st.mc[qb], pk[qb], blk[qb]);
+        // !(blk <= limit) also catches a NaN sum; no reference yet = first block
+        trig |= !(blk[qb] <= kPLimit) || st.m_ref[qb] == -INFINITY;
+      }
+      if (__any(trig)) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-#ifdef FA_X_NOSOFTMAX
-          pk[r] = (__builtin_bit_cast(uint32_t, s_cur[qb][2 * r]) & 0x3fff3fffu) ^ __builtin_bit_cast(uint32_t, s_cur[qb][2 * r + 1] + nmc);
-#else
-          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r], c, nmc));
-          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][2 * r + 1], c, nmc));
-          pk[r] = T::pack2(e0, e1);
-#endif
-        }
-        // the row sum is taken over the ROUNDED probabilities, the same numbers the
-        // matrix product uses, two per instruction
-        float l0 = st.lsum[qb], l1 = 0.f;
+        for (int qb = 0; qb < NQB; ++qb) {
+          // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
+          const float own = (!(blk[qb] <= kPLimit) || st.m_ref[qb] == -INFINITY) ? 1.f : 0.f;
+          const bool row_trig = sum_xor32(own) > 0.f;
+          float t0 = fmaxf(s_cur[qb][0], s_cur[qb][1]);
 #pragma unroll
-        for (int r = 0; r < 8; r += 2) {
-          l0 = T::sum2(pk[r], l0);
-          l1 = T::sum2(pk[r + 1], l1);
+          for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[qb][r]), s_cur[qb][r + 1]);
+          const float tmax = max_xor32(t0);
+          // the accumulator already holds P.V of the previous block (old reference)
+          rescale_rows<NQB>(st, qb, row_trig, tmax, c);
+          softmax_block(s_cur[qb], st.mc[qb], pk[qb], blk[qb]);
         }
-        st.lsum[qb] = l0 + l1;
-        p_cur[qb][0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
-        p_cur[qb][1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
+      }
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        st.lsum[qb] += blk[qb];
+        p_cur[qb][0] = as_v8<T>(make_uint4(pk[qb][0], pk[qb][1], pk[qb][2], pk[qb][3]));
+        p_cur[qb][1] = as_v8<T>(make_uint4(pk[qb][4], pk[qb][5], pk[qb][6], pk[qb][7]));
       }
     };
 
