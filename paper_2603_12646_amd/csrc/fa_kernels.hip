@@ -43,7 +43,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "fa_args.h"
+
+#ifndef FA_SCHED
+#define FA_SCHED 0
+#endif
 
 namespace {
 
@@ -469,12 +475,6 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
 // ======================================================================================
 // Global kernel: software pipeline over the full tiles + masked ragged tail
 // ======================================================================================
-template <class T, int NQB>
-struct PipeRegs {
-  floatx16 s[2][NQB];               // scores of the current / next block
-  typename T::v8 p[2][NQB][2];      // packed probabilities of the previous / current block
-};
-
 template <class T, int NQB, int WAVES_PER_EU>
 __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32 * NQB;
@@ -513,9 +513,17 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const int nf = n / kBN;  // full tiles: every key visible to every valid query
   const float c = a.c, tau_raw = a.tau_raw;
 
-  // Staging for the pipeline.  Iteration t of the pipeline works on score blocks
-  // u = 2t, 2t+1 (32 keys each) but touches K of blocks u+1 and V of blocks u-1, so the
-  // LDS "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t-32, 64t+32).
+  // The pipeline advances in UNITS: one unit = one 32-key block u against one of the
+  // wavefront's 32-query blocks qb, in the order (u,0) .. (u,NQB-1), (u+1,0) ...
+  // During a unit the vector ALU turns the unit's scores into probabilities while the
+  // matrix cores compute the NEXT unit's scores and add the PREVIOUS unit's P.V.
+  // K fragments of a key block are read from LDS once and serve all NQB query blocks;
+  // likewise the V^T fragments.
+  //
+  // Iteration t covers key blocks 2t, 2t+1.  It reads K of blocks 2t+1, 2t+2 (next
+  // unit's scores) and V of blocks 2t-1, 2t (NQB = 1) or 2t, 2t+1 (NQB = 2): the LDS
+  // "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t+kVShift, +64).
+  constexpr int kVShift = NQB == 1 ? -32 : 0;
   const int st_r = tid >> 3, st_c = (tid & 7) * 8;
   uint4 kst0, kst1, vst0, vst1;  // named registers: an array here ends up in scratch memory
   // Row bases are wavefront-uniform (scalar registers); each thread adds a fixed 32-bit
@@ -526,8 +534,8 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   auto fetch = [&](int t) {
     const int k0r = t * kBN + 32 < 0 ? 0 : t * kBN + 32;
     const int k1r = t * kBN + 64 > N - 32 ? N - 32 : t * kBN + 64;
-    const int v0r = t * kBN - 32 < 0 ? 0 : t * kBN - 32;
-    const int v1r = t * kBN < 0 ? 0 : t * kBN;
+    const int v0r = t * kBN + kVShift < 0 ? 0 : t * kBN + kVShift;
+    const int v1r = t * kBN + kVShift + 32 < 0 ? 0 : t * kBN + kVShift + 32;
     kst0 = *(const uint4*)(kp + (int64_t)k0r * a.ks[2] + koff);
     kst1 = *(const uint4*)(kp + (int64_t)k1r * a.ks[2] + koff);
     vst0 = *(const uint4*)(vp + (int64_t)v0r * a.vs[2] + voff);
@@ -540,36 +548,34 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     *(uint4*)&lds_v[buf * kBN * kSV + (32 + st_r) * kSV + st_c] = vst1;
   };
 
-  PipeRegs<T, NQB> pr;
+  // pipeline registers: scores of the current / next unit, packed probabilities of the
+  // previous / current unit, operand fragments of the key block in flight
+  floatx16 sA, sB;
+  typename T::v8 pA[2], pB[2], ka[4], va[2][2];
+  pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-    for (int ks2 = 0; ks2 < 2; ++ks2) pr.p[0][qb][ks2] = as_v8<T>(make_uint4(0, 0, 0, 0));
+  for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = as_v8<T>(make_uint4(0, 0, 0, 0));
 
   if (nf > 0) {
-    // prologue: block 0's scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
+    // prologue: unit (0,0)'s scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
     fetch(-1);
     stash(1);
     fetch(0);
     stash(0);
     __syncthreads();
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) pr.s[0][qb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) sA[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const typename T::v8 ka = load_k_frag<T>(&lds_k[kBN * kSK + 32 * kSK], l32, hh, ks);
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) pr.s[0][qb] = T::mfma(ka, qreg[qb][ks], pr.s[0][qb]);
+      ka[ks] = load_k_frag<T>(&lds_k[kBN * kSK + 32 * kSK], l32, hh, ks);
+      sA = T::mfma(ka[ks], qreg[0][ks], sA);
     }
     __syncthreads();  // stage 1 is overwritten at the end of iteration 0
 
-    // One pipeline step: probabilities of block `cur`, scores of the next block, P.V of
-    // the previous block.  The probabilities are formed against the row's current
-    // reference right away; the block's row-sum share doubles as the overflow sentinel
-    // (any p beyond kPLimit, an infinity included, pushes it over).  Only then - rarely -
-    // is the exact block maximum computed, the reference refreshed and the block redone.
+    // The probabilities are formed against the row's current reference right away; the
+    // lane's share of the block's row sum doubles as the overflow sentinel (any p beyond
+    // kPLimit, an infinity included, pushes it over).  Only then - rarely - is the exact
+    // block maximum computed, the reference refreshed and the block redone.
     auto softmax_block = [&](const floatx16& sv, float mcq, uint32_t (&pk)[8], float& blk) {
       const float nmc = -mcq;
 #pragma unroll
@@ -592,71 +598,59 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       }
       blk = l0 + l1;
     };
-    auto step = [&](floatx16 (&s_cur)[NQB], floatx16 (&s_nxt)[NQB], typename T::v8 (&p_prev)[NQB][2],
-                    typename T::v8 (&p_cur)[NQB][2], const uint16_t* kblk, const uint16_t* vblk) {
-      // -- matrix work of this step: next scores, previous P.V
-      typename T::v8 ka[4], va[2][2];
+    // One unit.  QB: query block of the current scores; NQ: query block of the next
+    // unit; PQ: query block of the previous unit; LOAD: this unit starts a new key block
+    // for both matrix products (fragments come from kblk / vblk), otherwise the
+    // fragments already in registers are reused.
+    auto unit = [&](auto QBc, auto NQc, auto PQc, auto LOADc, floatx16& s_cur, floatx16& s_nxt,
+                    typename T::v8 (&p_prev)[2], typename T::v8 (&p_cur)[2], const uint16_t* kblk,
+                    const uint16_t* vblk) {
+      constexpr int QB = decltype(QBc)::value, NQ = decltype(NQc)::value, PQ = decltype(PQc)::value;
+      constexpr bool LOAD = decltype(LOADc)::value;
+      if (LOAD) {
 #ifdef FA_X_NOLDS
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) ka[ks] = qreg[0][ks];
+        for (int ks = 0; ks < 4; ++ks) ka[ks] = qreg[0][ks];
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-        for (int db = 0; db < 2; ++db) va[ks2][db] = qreg[0][ks2 * 2 + db];
+        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = qreg[0][i];
 #else
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag<T>(kblk, l32, hh, ks);
+        for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag<T>(kblk, l32, hh, ks);
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-        for (int db = 0; db < 2; ++db) va[ks2][db] = load_vt_frag<T>(vblk, lane, ks2, db);
+        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = load_vt_frag<T>(vblk, lane, i >> 1, i & 1);
 #endif
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s_nxt[qb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) s_nxt[qb] = T::mfma(ka[ks], qreg[qb][ks], s_nxt[qb]);
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int qb = 0; qb < NQB; ++qb) st.oacc[qb][db] = T::mfma(va[ks2][db], p_prev[qb][ks2], st.oacc[qb][db]);
-      // -- vector work of this step: probabilities of the current block
-      uint32_t pk[NQB][8];
-      float blk[NQB];
-      bool trig = false;
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        softmax_block(s_cur[qb], st.mc[qb], pk[qb], blk[qb]);
-        // !(blk <= limit) also catches a NaN sum; no reference yet = first block
-        trig |= !(blk[qb] <= kPLimit) || st.m_ref[qb] == -INFINITY;
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+      // dependent products (the four k-steps of a score block, the two of an output
+      // block) alternate with independent ones
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s_nxt = T::mfma(ka[ks], qreg[NQ][ks], s_nxt);
+        st.oacc[PQ][ks & 1] = T::mfma(va[ks >> 1][ks & 1], p_prev[ks >> 1], st.oacc[PQ][ks & 1]);
+      }
+      uint32_t pk[8];
+      float blk;
+      softmax_block(s_cur, st.mc[QB], pk, blk);
+      // !(blk <= limit) also catches a NaN sum; no reference yet = first block
+      const bool trig = !(blk <= kPLimit) || st.m_ref[QB] == -INFINITY;
       if (__any(trig)) {
+        // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
+        const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
+        float t0 = fmaxf(s_cur[0], s_cur[1]);
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
-          const float own = (!(blk[qb] <= kPLimit) || st.m_ref[qb] == -INFINITY) ? 1.f : 0.f;
-          const bool row_trig = sum_xor32(own) > 0.f;
-          float t0 = fmaxf(s_cur[qb][0], s_cur[qb][1]);
-#pragma unroll
-          for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[qb][r]), s_cur[qb][r + 1]);
-          const float tmax = max_xor32(t0);
-          // the accumulator already holds P.V of the previous block (old reference)
-          rescale_rows<NQB>(st, qb, row_trig, tmax, c);
-          softmax_block(s_cur[qb], st.mc[qb], pk[qb], blk[qb]);
-        }
+        for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[r]), s_cur[r + 1]);
+        const float tmax = max_xor32(t0);
+        // the accumulator of this query block already holds P.V of all earlier key blocks
+        rescale_rows<NQB>(st, QB, row_trig, tmax, c);
+        softmax_block(s_cur, st.mc[QB], pk, blk);
       }
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        st.lsum[qb] += blk[qb];
-        p_cur[qb][0] = as_v8<T>(make_uint4(pk[qb][0], pk[qb][1], pk[qb][2], pk[qb][3]));
-        p_cur[qb][1] = as_v8<T>(make_uint4(pk[qb][4], pk[qb][5], pk[qb][6], pk[qb][7]));
-      }
+      st.lsum[QB] += blk;
+      p_cur[0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+      p_cur[1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
 
     int buf = 0;
     for (int t = 0; t < nf; ++t) {
@@ -666,8 +660,15 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       if (wave_has_rows) {
         const uint16_t* kt = &lds_k[buf * kBN * kSK];
         const uint16_t* vt = &lds_v[buf * kBN * kSV];
-        step(pr.s[0], pr.s[1], pr.p[0], pr.p[1], kt, vt);
-        step(pr.s[1], pr.s[0], pr.p[1], pr.p[0], kt + 32 * kSK, vt + 32 * kSV);
+        if constexpr (NQB == 1) {
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt);
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kSK, vt + 32 * kSV);
+        } else {
+          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt, vt);
+          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kSK, vt + 32 * kSV);
+        }
       }
 #ifndef FA_X_NOFETCH
       if (t + 1 < nf) stash(buf ^ 1);
@@ -705,15 +706,14 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   __syncthreads();
   if (wave_has_rows) {
     if (nf > 0) {
-      // after an even number of steps the pending probabilities sit in p[0]
+      // after an even number of units the pending probabilities sit in pA; they belong
+      // to the last full key block and the wavefront's last query block
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-          const typename T::v8 va = load_vt_frag<T>(lds_v, lane, ks2, db);
-#pragma unroll
-          for (int qb = 0; qb < NQB; ++qb)
-            st.oacc[qb][db] = T::mfma(va, pr.p[0][qb][ks2], st.oacc[qb][db]);
+          const typename T::v8 vf = load_vt_frag<T>(lds_v, lane, ks2, db);
+          st.oacc[NQB - 1][db] = T::mfma(vf, pA[ks2], st.oacc[NQB - 1][db]);
         }
     }
     if (tail > 0) {
@@ -743,7 +743,7 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   hipStream_t s = (hipStream_t)stream;
   const bool global = a.wl < 0 && a.wr < 0;
   if (global && v_path == 0) {
-    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 1>), dim3(grid), block, 0, s, a);
+    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
     if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
