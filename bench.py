@@ -153,6 +153,9 @@ def main():
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-others", action="store_true", help="time only the named workload")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 256 MiB three times, so a rocprofv3 "
+                         "--pmc run of this command has a kernel of known traffic to scale against")
     ap.add_argument("--tuning", type=lambda x: int(x, 0), default=0,
                     help="FA_TUNE_* bits forwarded to fa_fwd_ex (sweeps); 0 = library's choice")
     args = ap.parse_args()
@@ -199,6 +202,15 @@ def main():
                    "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning},
         "roofline": roof,
     }
+
+    if args.calibrate_copy:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)        # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        out["config"]["calibrate_copy_bytes_each_way"] = src.numel() * 2
+        del src, dst
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, lens, q, k, v)

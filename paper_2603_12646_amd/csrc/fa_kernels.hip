@@ -47,10 +47,6 @@
 
 #include "fa_args.h"
 
-#ifndef FA_SCHED
-#define FA_SCHED 0
-#endif
-
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -73,8 +69,9 @@ constexpr int kSK = kD + 8;
 constexpr int kSV = kD + 16;
 constexpr float kLn2 = 0.693147180559945309f;
 // A lane's 16 probabilities of one block may sum to at most this (against the row's
-// current reference) before the reference is refreshed; far inside fp16 range.
-constexpr float kPLimit = 1024.f;
+// current reference) before the reference is refreshed.  2^14 keeps every single p
+// inside fp16 range (max 65504) with room to spare and makes refreshes very rare.
+constexpr float kPLimit = 16384.f;
 
 struct F16 {
   typedef half8 v8;

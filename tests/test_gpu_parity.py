@@ -118,6 +118,12 @@ def test_increasing_scores_force_many_rescales():
         o_ref, lse_ref = attention_oracle(q, k[:, :, ::-1].copy(), v, None, 1.0)
         o, lse = run_simple(q, k[:, :, ::-1].copy(), v, None, dtype, 1.0)
         check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp down")
+        # steeper ramps: a block's probabilities against the stale reference overflow the
+        # storage type (scale 8) and even fp32 (scale 40) before the refresh catches them
+        for scale in (8.0, 40.0):
+            o_ref, lse_ref = attention_oracle(q, k, v, None, scale)
+            o, lse = run_simple(q, k, v, None, dtype, scale)
+            check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"steep ramp {scale}")
 
 
 def test_constant_v_and_zero_q_closed_forms():
