@@ -97,12 +97,12 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   a.wr = p->window_right < 0 ? -1 : (p->window_right >= p->max_len ? -1 : p->window_right);
   a.n_qtiles = (int32_t)n_qtiles;
   a.total_tiles = (int32_t)total;
-  // Tiles of one (batch, head) read the same K/V.  Keeping them on one XCD lets that
-  // XCD's L2 serve the re-reads (measured: 4.6x fewer bytes fetched from the fabric at 8K
-  // x 12 heads); it deals each XCD an equal COUNT of tiles, which is an equal amount of
-  // work only when all sequences have one length, so ragged batches keep the linear map.
-  const bool equal_lengths = p->batch == 1 || p->seq_lens == nullptr;
-  a.map_xcd = t_map == FA_TUNE_MAP_XCD ? 1 : (t_map == FA_TUNE_MAP_LINEAR ? 0 : (equal_lengths ? 1 : 0));
+  // Tiles of one (batch, head) read the same K/V; the XCD-aware order keeps them on one
+  // XCD's L2 (measured: 4.6x fewer bytes fetched from the fabric at 8K x 12 heads, same time).
+  a.map_xcd = t_map == FA_TUNE_MAP_LINEAR ? 0 : 1;
+  const int64_t per = ((int64_t)p->heads * n_qtiles + 7) / 8;
+  if (8 * per * p->batch > 0x7FFFFFF0LL) return FA_ERR_BAD_SHAPE;
+  a.xcd_per = (int32_t)per;
   const int v_path = t_v == FA_TUNE_V_SCALAR ? 1 : 0;
 
   return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, p->stream)

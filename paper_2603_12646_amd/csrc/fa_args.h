@@ -18,7 +18,8 @@ struct FaKernelArgs {
   int32_t wl, wr;   // window extents, < 0 = unbounded (already clamped to max_len)
   int32_t n_qtiles; // ceil(max_len / BM)
   int32_t total_tiles;  // batch * heads * n_qtiles
-  int32_t map_xcd;  // nonzero: consecutive tiles stay on one XCD
+  int32_t map_xcd;  // nonzero: each XCD owns a contiguous eighth of every batch element's tiles
+  int32_t xcd_per;  // ceil(heads * n_qtiles / 8)
 };
 
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.

@@ -271,18 +271,26 @@ struct TileCoord {
 
 template <int BM>
 __device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc) {
-  int tile = blockIdx.x;
   if (a.map_xcd) {
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // run of tiles so neighbours that share K/V share an L2.
-    const int per = (a.total_tiles + 7) >> 3;
-    tile = (tile & 7) * per + (tile >> 3);
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Tiles of
+    // one (batch, head) read the same K/V, so every XCD takes one contiguous eighth of each
+    // batch element's (head, query tile) range: K/V re-reads stay in that XCD's L2, and
+    // the eighths are equal work whatever the sequence lengths are.
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int per = a.xcd_per;                // ceil(heads * n_qtiles / 8)
+    tc.b = j / per;
+    const int t = x * per + (j - tc.b * per);
+    if (tc.b >= a.batch || t >= a.heads * a.n_qtiles) return false;
+    tc.h = t / a.n_qtiles;
+    tc.qt = t - tc.h * a.n_qtiles;
+  } else {
+    const int tile = blockIdx.x;
+    if (tile >= a.total_tiles) return false;
+    tc.qt = tile % a.n_qtiles;
+    const int bh = tile / a.n_qtiles;
+    tc.h = bh % a.heads;
+    tc.b = bh / a.heads;
   }
-  if (tile >= a.total_tiles) return false;
-  tc.qt = tile % a.n_qtiles;
-  const int bh = tile / a.n_qtiles;
-  tc.h = bh % a.heads;
-  tc.b = bh / a.heads;
   int n = a.max_len;
   if (a.seq_lens) {
     n = a.seq_lens[tc.b];
@@ -736,7 +744,7 @@ template <class T>
 int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   dim3 block(kThreads);
   unsigned grid = (unsigned)a.total_tiles;
-  if (a.map_xcd) grid = (unsigned)(((a.total_tiles + 7) / 8) * 8);
+  if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
   hipStream_t s = (hipStream_t)stream;
   const bool global = a.wl < 0 && a.wr < 0;
   if (global && v_path == 0) {
