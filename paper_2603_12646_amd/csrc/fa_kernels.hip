@@ -124,6 +124,23 @@ __device__ __forceinline__ float sum_xor32(float x) {
   return a + b;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane L's data lands at
+// lds_dst + 16*L (lds_dst wavefront-uniform), the global address is gbase (uniform, scalar
+// registers) + a per-lane byte offset.  Written as asm: the compiler would make every
+// later LDS read wait for such a load (it cannot tell that the stage being filled and the
+// stage being read are disjoint), which would serialise the prefetch.  The caller waits
+// with wait_direct_loads() before the barrier that publishes the stage.  M0 holds the LDS
+// address; the compiler reserves M0 and reloads it before each use of its own.
+__device__ __forceinline__ void load16_to_lds(const void* gbase, uint32_t lane_off_bytes, void* lds_dst) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  const uint32_t l = (uint32_t)(size_t)(lds_void*)lds_dst;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(l), "v"(lane_off_bytes), "s"(gbase)
+               : "memory");
+}
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
+
 template <class T>
 __device__ __forceinline__ typename T::v8 as_v8(uint4 u) {
   return __builtin_bit_cast(typename T::v8, u);
@@ -483,7 +500,9 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
 template <class T, int NQB, int WAVES_PER_EU>
 __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32 * NQB;
-  // the two stages of each array are contiguous: the tail treats lds_v as 128 rows
+  // Two stages of 64 x 128-byte rows during the pipeline; the ragged tail reuses the same
+  // storage with padded rows (K 64 x 144 B, V 96 x 160 B), which is why these arrays are
+  // sized by the padded strides.
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * kSK];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * kSV];
 
@@ -529,28 +548,51 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // unit's scores) and V of blocks 2t-1, 2t (NQB = 1) or 2t, 2t+1 (NQB = 2): the LDS
   // "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t+kVShift, +64).
   constexpr int kVShift = NQB == 1 ? -32 : 0;
-  const int st_r = tid >> 3, st_c = (tid & 7) * 8;
-  uint4 kst0, kst1, vst0, vst1;  // named registers: an array here ends up in scratch memory
-  // Row bases are wavefront-uniform (scalar registers); each thread adds a fixed 32-bit
-  // offset, so a tile fetch costs no vector address arithmetic.  Halves whose rows
-  // would leave [0, N) are only ever the unused ends of the pipeline (V before block 0,
-  // K after the last full block): their base is clamped, never their contents used.
-  const uint32_t koff = (uint32_t)(st_r * a.ks[2] + st_c), voff = (uint32_t)(st_r * a.vs[2] + st_c);
-  auto fetch = [&](int t) {
+  // Pipeline tiles go from HBM/L2 straight into LDS (global_load_lds, 16 bytes per lane):
+  // a wavefront's load fills 1 KB of LDS in lane order, i.e. 8 rows of 128 bytes, so the
+  // LDS tile is unpadded [64 rows][8 chunks of 16 bytes] and bank conflicts are avoided by
+  // choosing WHICH global chunk each lane fetches: chunk position c' of row r holds global
+  // chunk c' ^ (r & 7) for K (the 16-byte operand reads of 8 consecutive rows then hit 8
+  // different chunk positions) and c' ^ 2(r & 3) for V (the four rows x two chunks of a
+  // transpose read hit 8 different positions).  Wavefront w moves rows 8w..8w+7 of each
+  // 32-row half.  Row bases are wavefront-uniform; each lane adds a fixed offset.  Halves
+  // whose rows would leave [0, N) are only ever the unused ends of the pipeline (V before
+  // block 0, K after the last full block): their base is clamped, their contents unused.
+  const int dl_r = 8 * wave + (lane >> 3);  // row within a 32-row half
+  const uint32_t koff = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane & 7) ^ (lane >> 3)) * 8));  // bytes
+  const uint32_t voff = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8));
+  auto fetch = [&](int t, uint16_t* kstage, uint16_t* vstage) {
     const int k0r = t * kBN + 32 < 0 ? 0 : t * kBN + 32;
     const int k1r = t * kBN + 64 > N - 32 ? N - 32 : t * kBN + 64;
     const int v0r = t * kBN + kVShift < 0 ? 0 : t * kBN + kVShift;
     const int v1r = t * kBN + kVShift + 32 < 0 ? 0 : t * kBN + kVShift + 32;
-    kst0 = *(const uint4*)(kp + (int64_t)k0r * a.ks[2] + koff);
-    kst1 = *(const uint4*)(kp + (int64_t)k1r * a.ks[2] + koff);
-    vst0 = *(const uint4*)(vp + (int64_t)v0r * a.vs[2] + voff);
-    vst1 = *(const uint4*)(vp + (int64_t)v1r * a.vs[2] + voff);
+    uint16_t* kdst = kstage + 8 * wave * kD;
+    uint16_t* vdst = vstage + 8 * wave * kD;
+    load16_to_lds(kp + (int64_t)k0r * a.ks[2], koff, kdst);
+    load16_to_lds(kp + (int64_t)k1r * a.ks[2], koff, kdst + 32 * kD);
+    load16_to_lds(vp + (int64_t)v0r * a.vs[2], voff, vdst);
+    load16_to_lds(vp + (int64_t)v1r * a.vs[2], voff, vdst + 32 * kD);
   };
-  auto stash = [&](int buf) {
-    *(uint4*)&lds_k[buf * kBN * kSK + st_r * kSK + st_c] = kst0;
-    *(uint4*)&lds_k[buf * kBN * kSK + (32 + st_r) * kSK + st_c] = kst1;
-    *(uint4*)&lds_v[buf * kBN * kSV + st_r * kSV + st_c] = vst0;
-    *(uint4*)&lds_v[buf * kBN * kSV + (32 + st_r) * kSV + st_c] = vst1;
+  // per-lane fragment offsets (16-bit elements) into a 32-row block of a swizzled tile
+  uint32_t kfo[4], vfo[2];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) kfo[ks] = l32 * kD + (((2 * ks + hh) ^ (l32 & 7)) * 8);
+  {
+    const int p16 = lane & 15, g = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+      vfo[db] = (4 * hh + (p16 >> 2)) * kD + (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ (2 * (p16 >> 2))) * 8) +
+                (p16 & 1) * 4;
+  }
+  auto k_frag = [&](const uint16_t* kblk, int ks) { return as_v8<T>(*(const uint4*)&kblk[kfo[ks]]); };
+  auto vt_frag = [&](const uint16_t* vblk, int ks2, int db) {
+    typedef __attribute__((address_space(3))) shortx4 lds_s4;
+    const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + ks2 * 16 * kD]);
+    const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + (ks2 * 16 + 8) * kD]);
+    shortx8 x;
+    x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
+    x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
+    return __builtin_bit_cast(typename T::v8, x);
   };
 
   // pipeline registers: scores of the current / next unit, packed probabilities of the
@@ -563,19 +605,18 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
 
   if (nf > 0) {
     // prologue: unit (0,0)'s scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
-    fetch(-1);
-    stash(1);
-    fetch(0);
-    stash(0);
+    fetch(-1, &lds_k[kBN * kD], &lds_v[kBN * kD]);
+    fetch(0, lds_k, lds_v);
+    wait_direct_loads();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) sA[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      ka[ks] = load_k_frag<T>(&lds_k[kBN * kSK + 32 * kSK], l32, hh, ks);
+      ka[ks] = k_frag(&lds_k[kBN * kD + 32 * kD], ks);
       sA = T::mfma(ka[ks], qreg[0][ks], sA);
     }
-    __syncthreads();  // stage 1 is overwritten at the end of iteration 0
+    __syncthreads();  // stage 1 is refilled during iteration 0
 
     // The probabilities are formed against the row's current reference right away; the
     // lane's share of the block's row sum doubles as the overflow sentinel (any p beyond
@@ -620,9 +661,9 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = qreg[0][i];
 #else
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag<T>(kblk, l32, hh, ks);
+        for (int ks = 0; ks < 4; ++ks) ka[ks] = k_frag(kblk, ks);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = load_vt_frag<T>(vblk, lane, i >> 1, i & 1);
+        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = vt_frag(vblk, i >> 1, i & 1);
 #endif
       }
 #pragma unroll
@@ -657,30 +698,34 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
-    int buf = 0;
-    for (int t = 0; t < nf; ++t) {
+    auto iter = [&](int t, uint16_t* kfill, uint16_t* vfill, const uint16_t* kt, const uint16_t* vt) {
 #ifndef FA_X_NOFETCH
-      if (t + 1 < nf) fetch(t + 1);
+      // the stage being filled was last read in iteration t-1; every wavefront is past
+      // that iteration's barrier
+      if (t + 1 < nf) fetch(t + 1, kfill, vfill);
 #endif
       if (wave_has_rows) {
-        const uint16_t* kt = &lds_k[buf * kBN * kSK];
-        const uint16_t* vt = &lds_v[buf * kBN * kSV];
         if constexpr (NQB == 1) {
           unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kSK, vt + 32 * kSV);
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kD, vt + 32 * kD);
         } else {
           unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
           unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt, vt);
           unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kSK, vt + 32 * kSV);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kD, vt + 32 * kD);
         }
       }
 #ifndef FA_X_NOFETCH
-      if (t + 1 < nf) stash(buf ^ 1);
+      wait_direct_loads();  // this wavefront's share of the next tile has landed
 #endif
 #ifndef FA_X_NOBARRIER
       __syncthreads();
 #endif
+    };
+    int buf = 0;
+    for (int t = 0; t < nf; ++t) {
+      iter(t, &lds_k[(buf ^ 1) * kBN * kD], &lds_v[(buf ^ 1) * kBN * kD], &lds_k[buf * kBN * kD],
+           &lds_v[buf * kBN * kD]);
       buf ^= 1;
     }
   }
