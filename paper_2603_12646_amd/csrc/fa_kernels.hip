@@ -573,6 +573,26 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     load16_to_lds(vp + (int64_t)v0r * a.vs[2], voff, vdst);
     load16_to_lds(vp + (int64_t)v1r * a.vs[2], voff, vdst + 32 * kD);
   };
+  // Inside the pipeline loop the four row bases just advance by one tile per iteration
+  // (scalar 64-bit adds); only the very last tile's second K half can need the clamp.
+  const uint16_t* kg0 = kp + (int64_t)(kBN + 32) * a.ks[2];
+  const uint16_t* kg1 = kp + (int64_t)(kBN + 64) * a.ks[2];
+  const uint16_t* vg0 = vp + (int64_t)(kBN + kVShift) * a.vs[2];
+  const uint16_t* vg1 = vp + (int64_t)(kBN + kVShift + 32) * a.vs[2];
+  const int k1_last_row = n / kBN * kBN > N - 32 ? N - 32 : n / kBN * kBN;  // tile nf-1: min(64 nf, N-32)
+  const uint16_t* kg1_last = kp + (int64_t)k1_last_row * a.ks[2];
+  auto fetch_next = [&](bool last, uint16_t* kstage, uint16_t* vstage) {
+    uint16_t* kdst = kstage + 8 * wave * kD;
+    uint16_t* vdst = vstage + 8 * wave * kD;
+    load16_to_lds(kg0, koff, kdst);
+    load16_to_lds(last ? kg1_last : kg1, koff, kdst + 32 * kD);
+    load16_to_lds(vg0, voff, vdst);
+    load16_to_lds(vg1, voff, vdst + 32 * kD);
+    kg0 += kBN * a.ks[2];
+    kg1 += kBN * a.ks[2];
+    vg0 += kBN * a.vs[2];
+    vg1 += kBN * a.vs[2];
+  };
   // per-lane fragment offsets (16-bit elements) into a 32-row block of a swizzled tile
   uint32_t kfo[4], vfo[2];
 #pragma unroll
@@ -698,11 +718,16 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
-    auto iter = [&](int t, uint16_t* kfill, uint16_t* vfill, const uint16_t* kt, const uint16_t* vt) {
+    // One iteration on LDS stage STAGE (a compile-time constant, so every LDS address is a
+    // per-lane register plus an immediate); the other stage is being filled meanwhile.
+    auto iter = [&](auto STAGEc, int t) {
+      constexpr int STAGE = decltype(STAGEc)::value;
+      const uint16_t* kt = &lds_k[STAGE * kBN * kD];
+      const uint16_t* vt = &lds_v[STAGE * kBN * kD];
 #ifndef FA_X_NOFETCH
       // the stage being filled was last read in iteration t-1; every wavefront is past
       // that iteration's barrier
-      if (t + 1 < nf) fetch(t + 1, kfill, vfill);
+      if (t + 1 < nf) fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * kD], &lds_v[(STAGE ^ 1) * kBN * kD]);
 #endif
       if (wave_has_rows) {
         if constexpr (NQB == 1) {
@@ -722,12 +747,12 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       __syncthreads();
 #endif
     };
-    int buf = 0;
-    for (int t = 0; t < nf; ++t) {
-      iter(t, &lds_k[(buf ^ 1) * kBN * kD], &lds_v[(buf ^ 1) * kBN * kD], &lds_k[buf * kBN * kD],
-           &lds_v[buf * kBN * kD]);
-      buf ^= 1;
+    int t = 0;
+    for (; t + 1 < nf; t += 2) {
+      iter(I0{}, t);
+      iter(I1{}, t + 1);
     }
+    if (t < nf) iter(I0{}, t);
   }
 
   // ---- drain + ragged tail -------------------------------------------------------------
@@ -794,7 +819,10 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   if (global && v_path == 0) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
+#ifndef FA_X_WPE
+#define FA_X_WPE 2
+#endif
+    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, FA_X_WPE>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
     if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
