@@ -183,6 +183,28 @@ __device__ __forceinline__ typename T::v8 load_vt_frag_scalar(const uint16_t* vb
   return __builtin_bit_cast(typename T::v8, x);
 }
 
+// The same two operands from an UNPADDED, swizzled tile (64 halves per row), the layout
+// that direct global->LDS loads produce: 16-byte chunk position c' of row r holds logical
+// chunk c' ^ (r & 7) for K and c' ^ 2(r & 3) for V.  kblk / vblk must start at a row that
+// is a multiple of 8.
+template <class T>
+__device__ __forceinline__ typename T::v8 load_k_frag_swz(const uint16_t* kblk, int l32, int hh, int ks) {
+  return as_v8<T>(*(const uint4*)&kblk[l32 * kD + (((2 * ks + hh) ^ (l32 & 7)) * 8)]);
+}
+template <class T>
+__device__ __forceinline__ typename T::v8 load_vt_frag_swz(const uint16_t* vblk, int lane, int ks2, int db) {
+  const int hh = lane >> 5, p16 = lane & 15, g = (lane >> 4) & 1;
+  const int row = ks2 * 16 + 4 * hh + (p16 >> 2);
+  const int off = (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ (2 * (p16 >> 2))) * 8) + (p16 & 1) * 4;
+  typedef __attribute__((address_space(3))) shortx4 lds_s4;
+  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * kD + off]);
+  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * kD + off]);
+  shortx8 x;
+  x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
+  x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
+  return __builtin_bit_cast(typename T::v8, x);
+}
+
 template <int NQB>
 struct RowState {
   floatx16 oacc[NQB][2];  // O^T: [qb][d block], rows d = 32*db + 8*(r/4) + 4*hh + r%4
@@ -212,8 +234,10 @@ __device__ __forceinline__ void rescale_rows(RowState<NQB>& st, int qb, bool ref
 
 // One 32-key block, scores to accumulator, with per-element masking if MASKED.
 // kblk / vblk: LDS rows of the block; kb0: its first key index; [jlo, jhi] per lane
-// is the visible key range of the lane's query.
-template <class T, int NQB, bool MASKED, bool V_TR>
+// is the visible key range of the lane's query.  FRAG selects how operands come out of
+// LDS: 0 padded tile + transpose read, 1 padded tile + 16-bit reads, 2 swizzled tile +
+// transpose read.
+template <class T, int NQB, bool MASKED, int FRAG>
 __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T::v8 (&qreg)[NQB][4],
                                              const uint16_t* kblk, const uint16_t* vblk, int kb0,
                                              const int (&jlo)[NQB], const int (&jhi)[NQB], int lane,
@@ -226,7 +250,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T
     for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    const typename T::v8 ka = load_k_frag<T>(kblk, l32, hh, ks);
+    const typename T::v8 ka = FRAG == 2 ? load_k_frag_swz<T>(kblk, l32, hh, ks) : load_k_frag<T>(kblk, l32, hh, ks);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) sacc[qb] = T::mfma(ka, qreg[qb][ks], sacc[qb]);
   }
@@ -269,8 +293,9 @@ __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T
   for (int ks2 = 0; ks2 < 2; ++ks2) {
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
-      const typename T::v8 va = V_TR ? load_vt_frag<T>(vblk, lane, ks2, db)
-                                     : load_vt_frag_scalar<T>(vblk, lane, ks2, db);
+      const typename T::v8 va = FRAG == 2   ? load_vt_frag_swz<T>(vblk, lane, ks2, db)
+                                : FRAG == 0 ? load_vt_frag<T>(vblk, lane, ks2, db)
+                                            : load_vt_frag_scalar<T>(vblk, lane, ks2, db);
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         const uint4 pu = make_uint4(pk[qb][ks2 * 4 + 0], pk[qb][ks2 * 4 + 1], pk[qb][ks2 * 4 + 2],
@@ -363,18 +388,25 @@ __device__ __forceinline__ void init_state(RowState<NQB>& st) {
   }
 }
 
+// Epilogue: o = O / l, cast, store; lse.  A lane holds one output ROW in pieces of four
+// columns, so storing from registers would scatter 8-byte pieces over 32 rows per
+// instruction.  Each wavefront instead transposes its 32 x 64 block through a private
+// LDS patch (rows padded to 144 bytes) and stores whole 128-byte rows, 16 bytes per lane.
+// wave_patch: kEpiPatch 16-bit elements of LDS owned by this wavefront; the caller has
+// made sure (barrier) that nobody still reads tiles from that memory.
+constexpr int kEpiStride = kD + 8;
+constexpr int kEpiPatch = 32 * kEpiStride;
+
 template <class T, int NQB>
 __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& st, uint16_t* op, float* lsep,
-                                         int qw0, int n, int lane) {
+                                         int qw0, int n, int lane, uint16_t* wave_patch) {
   const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int ig = qw0 + qb * 32 + l32;
     const float ltot = sum_xor32(st.lsum[qb]);
-    if (ig >= N) continue;
     const bool live = (ig < n) && (ltot > 0.f);
     const float inv = live ? 1.0f / ltot : 0.f;
-    uint16_t* orow = op + ig * a.os[2];
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -382,11 +414,19 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& s
         uint2 w;
         w.x = T::pack2(st.oacc[qb][db][4 * g + 0] * inv, st.oacc[qb][db][4 * g + 1] * inv);
         w.y = T::pack2(st.oacc[qb][db][4 * g + 2] * inv, st.oacc[qb][db][4 * g + 3] * inv);
-        if (!live) w = make_uint2(0, 0);
-        *(uint2*)(orow + db * 32 + 8 * g + 4 * hh) = w;
+        if (!live) w = make_uint2(0, 0);  // padded rows and rows with no visible key
+        *(uint2*)&wave_patch[l32 * kEpiStride + db * 32 + 8 * g + 4 * hh] = w;
       }
     }
-    if (lsep && hh == 0)
+    // same wavefront writes and reads the patch: program order is enough
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int r = pass * 8 + (lane >> 3);
+      const uint4 v = *(const uint4*)&wave_patch[r * kEpiStride + (lane & 7) * 8];
+      const int row = qw0 + qb * 32 + r;
+      if (row < N) *(uint4*)(op + row * a.os[2] + (lane & 7) * 8) = v;
+    }
+    if (lsep && hh == 0 && ig < N)
       lsep[ig] = live ? (st.mc[qb] + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
   }
 }
@@ -483,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
         if (kb0 >= n) continue;
         if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
         if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
-        simple_block<T, NQB, true, V_TR>(st, qreg, &lds_k[buf][kb * 32 * kSK], &lds_v[buf][kb * 32 * kSV],
+        simple_block<T, NQB, true, V_TR ? 0 : 1>(st, qreg, &lds_k[buf][kb * 32 * kSK], &lds_v[buf][kb * 32 * kSV],
                                          kb0, jlo, jhi, lane, a.c, a.tau_raw);
       }
     }
@@ -491,7 +531,131 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
     __syncthreads();
     buf ^= 1;
   }
-  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane);
+  // the loop ended with a barrier: the K stages are free
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, &lds_k[0][0] + wave * kEpiPatch);
+}
+
+// ======================================================================================
+// Window kernel: local layers.  The key range of a 128-row query tile is only a few
+// hundred keys, so the work is bound by getting K/V (and Q, O) through HBM once and by
+// latency: K/V move in 32-key blocks through a ring of kWinStages LDS stages filled by
+// direct global->LDS loads, kWinStages - 1 blocks ahead of the arithmetic (small stages
+// keep several workgroups per compute unit AND several blocks per workgroup in flight).
+// A wavefront multiplies only the blocks its own 32 queries can see; blocks it sees
+// completely skip the mask work.  One barrier per block.
+// ======================================================================================
+#ifndef FA_X_WINSTAGES
+#define FA_X_WINSTAGES 4
+#endif
+constexpr int kWinStages = FA_X_WINSTAGES;
+constexpr int kWinBN = 32;  // keys per stage
+
+template <class T>
+__global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKernelArgs a) {
+  constexpr int BM = kWaves * 32;
+  // at least the four 32 x 72 epilogue patches must fit in lds_k
+  constexpr int kStageElems = kWinBN * kD;
+  constexpr int kKElems = kWinStages * kStageElems > kWaves * kEpiPatch ? kWinStages * kStageElems : kWaves * kEpiPatch;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kKElems];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWinStages * kStageElems];
+
+  TileCoord tc;
+  if (!locate_tile<BM>(a, tc)) return;
+  const int N = a.max_len, n = tc.n, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  if (q0 >= n) {
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+
+  // key range of this workgroup, in 32-key blocks
+  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  int lo = 0, hi = n;
+  if (a.wl >= 0) lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
+  if (a.wr >= 0) hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
+  const int t_lo = lo / kWinBN;
+  const int t_hi = (hi + kWinBN - 1) / kWinBN;
+
+  // Block t goes to stage t % kWinStages.  Wavefront w moves rows 8w..8w+7 of the block
+  // (one 1 KB load each for K and V); a lane's row is clamped to the last row of the
+  // tensor (rows >= n are masked or zeroed below), so its global offset is a per-lane
+  // 32-bit byte offset from the (batch, head) slice.
+  const int dl_r = 8 * wave + (lane >> 3);
+  const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ (lane >> 3)) * 8);
+  const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8);
+  const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
+  auto issue_block = [&](int t) {
+    const int stage = t % kWinStages;
+    const int jg = t * kWinBN + dl_r;
+    const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+    load16_to_lds(kp, jc * krow_b + kchunk, &lds_k[stage * kStageElems + 8 * wave * kD]);
+    load16_to_lds(vp, jc * vrow_b + vchunk, &lds_v[stage * kStageElems + 8 * wave * kD]);
+  };
+  // After a block has landed: V rows at or beyond n are overwritten with zeros by the
+  // lanes that fetched them (0 * whatever is stored in the padding must be 0).
+  auto scrub_block = [&](int t) {
+    if (t * kWinBN + kWinBN <= n) return;
+    if (t * kWinBN + dl_r >= n)
+      *(uint4*)&lds_v[(t % kWinStages) * kStageElems + dl_r * kD + (lane & 7) * 8] = make_uint4(0, 0, 0, 0);
+  };
+
+  // prologue: kWinStages - 1 blocks in flight before anything else
+#pragma unroll
+  for (int i = 0; i < kWinStages - 1; ++i)
+    if (t_lo + i < t_hi) issue_block(t_lo + i);
+
+  const int qw0 = q0 + wave * 32;
+  const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
+  const bool wave_has_rows = qw_last >= qw0;
+  typename T::v8 qreg[1][4];
+  load_q<T, 1>(a, qp, qw0, lane, qreg);
+  RowState<1> st;
+  init_state<1>(st);
+  int jlo[1], jhi[1];
+  {
+    const int ig = qw0 + l32;
+    jlo[0] = 0;
+    jhi[0] = n - 1;
+    if (a.wl >= 0 && ig - a.wl > jlo[0]) jlo[0] = ig - a.wl;
+    if (a.wr >= 0 && ig + a.wr < jhi[0]) jhi[0] = ig + a.wr;
+  }
+
+  for (int t = t_lo; t < t_hi; ++t) {
+    // Each block is 2 loads per wavefront, and loads complete in order: block t has landed
+    // once at most 2 * (number of younger blocks in flight) loads are outstanding.
+    const int younger = (t_hi - 1 - t < kWinStages - 2 ? t_hi - 1 - t : kWinStages - 2);
+    if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    scrub_block(t);
+    __syncthreads();
+    // stage (t-1) % kWinStages is free now: every wavefront finished block t-1 before this barrier
+    if (t + kWinStages - 1 < t_hi) issue_block(t + kWinStages - 1);
+    const int kb0 = t * kWinBN;
+    // wavefront-uniform: skip key blocks no query of this wavefront sees
+    if (!wave_has_rows || kb0 >= n) continue;
+    if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
+    if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
+    // blocks every valid query of the wavefront sees completely need no mask work
+    const bool interior = kb0 + 32 <= n && (a.wl < 0 || kb0 >= qw_last - a.wl) &&
+                          (a.wr < 0 || kb0 + 31 <= qw0 + a.wr);
+    const uint16_t* kblk = &lds_k[(t % kWinStages) * kStageElems];
+    const uint16_t* vblk = &lds_v[(t % kWinStages) * kStageElems];
+    if (interior) simple_block<T, 1, false, 2>(st, qreg, kblk, vblk, kb0, jlo, jhi, lane, a.c, a.tau_raw);
+    else simple_block<T, 1, true, 2>(st, qreg, kblk, vblk, kb0, jlo, jhi, lane, a.c, a.tau_raw);
+  }
+  __syncthreads();  // all blocks consumed: the K stages become the epilogue patches
+  epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
 }
 
 // ======================================================================================
@@ -802,12 +966,13 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       for (int kb = 0; kb < 2; ++kb) {
         const int kb0 = nf * kBN + kb * 32;
         if (kb0 >= n) continue;
-        simple_block<T, NQB, true, true>(st, qreg, &lds_k[kb * 32 * kSK], &lds_v[(32 + kb * 32) * kSV], kb0,
+        simple_block<T, NQB, true, 0>(st, qreg, &lds_k[kb * 32 * kSK], &lds_v[(32 + kb * 32) * kSV], kb0,
                                          jlo, jhi, lane, c, tau_raw);
       }
     }
   }
-  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane);
+  __syncthreads();  // tail consumed: the K storage becomes the epilogue patches
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
 }
 
 template <class T>
@@ -817,12 +982,13 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
   hipStream_t s = (hipStream_t)stream;
   const bool global = a.wl < 0 && a.wr < 0;
+  // per-lane 32-bit byte offsets into a (batch, head) slice
+  const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
   if (global && v_path == 0) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
-#ifndef FA_X_WPE
-#define FA_X_WPE 2
-#endif
-    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, FA_X_WPE>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
+  } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
+    hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
     if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
