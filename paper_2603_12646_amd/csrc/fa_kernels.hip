@@ -10,8 +10,9 @@
 //   * a workgroup owns BM = 4*32*NQB query rows of one (batch, head); each
 //     wavefront owns NQB blocks of 32 query rows and keeps their Q fragments,
 //     running maximum / sum and the 64-wide output accumulator in registers;
-//   * K and V are streamed through LDS in tiles of 64 keys, double buffered,
-//     fetched from HBM/L2 with 16-byte loads one tile ahead of the arithmetic.
+//   * K and V are streamed through LDS, fetched from HBM/L2 ahead of the arithmetic
+//     (in the main kernels with direct global->LDS loads into an unpadded, XOR-swizzled
+//     tile; in the reference masked kernel through registers into a padded tile).
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_{f16,bf16}, D = A * B + C with
 // A: 32 x 16, B: 16 x 32, C: 32 x 32; lane l holds A[l%32][8*(l/32)..+7],
@@ -33,13 +34,17 @@
 // than a threshold (2^8 in p); rescaling the accumulator is then rare, and the
 // result is unchanged because numerator and denominator share the reference.
 //
-// Two kernels:
+// Kernels:
 //   fa_fwd_global_kernel  global layers (no window).  Full 64-key tiles run in a
-//       software pipeline over 32-key blocks: while the vector ALU turns block u's
-//       scores into probabilities, the matrix cores compute block u+1's scores and
-//       accumulate block u-1's P.V.  The ragged last tile takes the masked path.
-//   fa_fwd_masked_kernel  local-window layers (and one-sided windows): every tile
-//       is masked per element, and key blocks outside a wavefront's band are skipped.
+//       software pipeline over 32-key x 32-query units: while the vector ALU turns unit
+//       w's scores into probabilities, the matrix cores compute unit w+1's scores and
+//       accumulate unit w-1's P.V.  The ragged last tile takes the masked block.
+//   fa_fwd_window_resident_kernel  local layers whose key range per query tile fits in
+//       LDS (the paper's 63/64 window): everything is requested at once, then each
+//       wavefront runs the same pipeline over the blocks its queries can see.
+//   fa_fwd_window_kernel  wider or one-sided windows: ring of 32-key stages.
+//   fa_fwd_masked_kernel  reference path (register staging, padded tiles, optional
+//       16-bit V reads), kept as an independent implementation for the tests.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -75,6 +80,7 @@ constexpr float kPLimit = 16384.f;
 
 struct F16 {
   typedef half8 v8;
+  static constexpr bool kSumRounded = true;
   static __device__ __forceinline__ floatx16 mfma(v8 a, v8 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
   }
@@ -90,6 +96,7 @@ struct F16 {
 
 struct BF16 {
   typedef bf8 v8;
+  static constexpr bool kSumRounded = false;
   static __device__ __forceinline__ floatx16 mfma(v8 a, v8 b, floatx16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
   }
@@ -230,6 +237,52 @@ __device__ __forceinline__ void rescale_rows(RowState<NQB>& st, int qb, bool ref
   for (int db = 0; db < 2; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha;
+}
+
+// Probabilities of one 32 x 32 block against the row's current reference, rounded and
+// packed as the B operand of the P.V product, plus the lane's share of their row sum.
+// fp16: the sum is taken over the ROUNDED probabilities (the numbers the matrix product
+// uses), two per v_dot2c instruction.  bf16: the unrounded fp32 values are summed; with
+// 8 mantissa bits the rounded sum would cost lse up to ~2e-3 when a row sees only a
+// handful of keys.  vis: bit r set = accumulator element r is a visible key.
+template <class T, bool MASKED>
+__device__ __forceinline__ void prob_block(const floatx16& sv, float c, float mcq, uint32_t vis,
+                                           uint32_t (&pk)[8], float& blk) {
+  const float nmc = -mcq;
+  float l0 = 0.f, l1 = 0.f;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r], c, nmc));
+    float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r + 1], c, nmc));
+    if (MASKED) {
+      e0 = (vis >> (2 * r) & 1) ? e0 : 0.f;
+      e1 = (vis >> (2 * r + 1) & 1) ? e1 : 0.f;
+    }
+    pk[r] = T::pack2(e0, e1);
+    if (!T::kSumRounded) {
+      l0 += e0;
+      l1 += e1;
+    }
+  }
+  if (T::kSumRounded) {
+#pragma unroll
+    for (int r = 0; r < 8; r += 2) {
+      l0 = T::sum2(pk[r], l0);
+      l1 = T::sum2(pk[r + 1], l1);
+    }
+  }
+  blk = l0 + l1;
+}
+
+// Visibility bits of a lane's 16 accumulator elements for the block starting at key kb0.
+__device__ __forceinline__ uint32_t visible_bits(int kb0, int hh, int jlo, int jhi) {
+  uint32_t vis = 0;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int jg = kb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
+    vis |= (jg >= jlo && jg <= jhi) ? (1u << r) : 0u;
+  }
+  return vis;
 }
 
 // One 32-key block, scores to accumulator, with per-element masking if MASKED.
@@ -544,10 +597,7 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
 // A wavefront multiplies only the blocks its own 32 queries can see; blocks it sees
 // completely skip the mask work.  One barrier per block.
 // ======================================================================================
-#ifndef FA_X_WINSTAGES
-#define FA_X_WINSTAGES 4
-#endif
-constexpr int kWinStages = FA_X_WINSTAGES;
+constexpr int kWinStages = 4;
 constexpr int kWinBN = 32;  // keys per stage
 
 template <class T>
@@ -655,6 +705,179 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
     else simple_block<T, 1, true, 2>(st, qreg, kblk, vblk, kb0, jlo, jhi, lane, a.c, a.tau_raw);
   }
   __syncthreads();  // all blocks consumed: the K stages become the epilogue patches
+  epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
+}
+
+// ======================================================================================
+// Resident window kernel: local layers whose whole key range per 128-row query tile fits
+// in kResBlocks 32-key blocks of LDS (the paper's 63/64 window needs exactly 8).  All of
+// the tile's K/V is requested at once with direct global->LDS loads, one barrier
+// publishes it, and then every wavefront runs the same software pipeline as the global
+// kernel over just the blocks its own 32 queries can see - next block's scores and the
+// previous block's P.V on the matrix cores while the vector ALU forms this block's
+// probabilities - with mask work only on the blocks that are cut by the window or the
+// sequence end.  No further barriers until the epilogue.
+// ======================================================================================
+constexpr int kResBlocks = 8;
+
+template <class T>
+__global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(const FaKernelArgs a) {
+  constexpr int BM = kWaves * 32;
+  constexpr int kBlk = 32 * kD;  // elements per block
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kResBlocks * kBlk];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kResBlocks * kBlk];
+
+  TileCoord tc;
+  if (!locate_tile<BM>(a, tc)) return;
+  const int N = a.max_len, n = tc.n, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  if (q0 >= n) {
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+
+  // key range of this workgroup, in 32-key blocks; block b lives in slot b - b_lo
+  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  const int lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
+  const int hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
+  const int b_lo = lo >> 5;
+  int b_hi = (hi + 31) >> 5;
+  if (b_hi > b_lo + kResBlocks) b_hi = b_lo + kResBlocks;  // never true for the windows the host routes here
+
+  // Wavefront w moves rows 8w..8w+7 of every block (one 1 KB load each for K and V).  A
+  // lane's row is clamped to the last row of the tensor (rows >= n are masked or zeroed
+  // below), so its global offset is a per-lane 32-bit byte offset from the slice.
+  const int dl_r = 8 * wave + (lane >> 3);
+  {
+    const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ (lane >> 3)) * 8);
+    const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8);
+    const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
+#pragma unroll
+    for (int i = 0; i < kResBlocks; ++i) {
+      if (b_lo + i < b_hi) {
+        const int jg = (b_lo + i) * 32 + dl_r;
+        const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+        load16_to_lds(kp, jc * krow_b + kchunk, &lds_k[i * kBlk + 8 * wave * kD]);
+        load16_to_lds(vp, jc * vrow_b + vchunk, &lds_v[i * kBlk + 8 * wave * kD]);
+      }
+    }
+  }
+
+  const int qw0 = q0 + wave * 32;
+  const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
+  const bool wave_has_rows = qw_last >= qw0;
+  typename T::v8 qreg[1][4];
+  load_q<T, 1>(a, qp, qw0, lane, qreg);
+  RowState<1> st;
+  init_state<1>(st);
+  const int ig = qw0 + l32;
+  const bool alive = ig < n;
+  int jlo = ig - a.wl > 0 ? ig - a.wl : 0;
+  int jhi = ig + a.wr < n - 1 ? ig + a.wr : n - 1;
+  const float c = a.c;
+
+  wait_direct_loads();
+  // V rows at or beyond n are overwritten with zeros by the lanes that fetched them
+  // (0 * whatever is stored in the padding must be 0); only the last block can have any
+  {
+    const int i = b_hi - 1 - b_lo;
+    if ((b_hi - 1) * 32 + dl_r >= n) *(uint4*)&lds_v[i * kBlk + dl_r * kD + (lane & 7) * 8] = make_uint4(0, 0, 0, 0);
+  }
+  __syncthreads();
+
+  if (wave_has_rows) {
+    // blocks this wavefront's queries can see
+    int fb = (qw0 - a.wl) >> 5;
+    fb = fb < b_lo ? b_lo : fb;
+    int lb = (qw_last + a.wr) >> 5;
+    lb = lb > b_hi - 1 ? b_hi - 1 : lb;
+
+    floatx16 sA, sB;
+    typename T::v8 pA[2], pB[2];
+    pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sA[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      sA = T::mfma(load_k_frag_swz<T>(&lds_k[(fb - b_lo) * kBlk], l32, hh, ks), qreg[0][ks], sA);
+
+    // One unit of the pipeline: probabilities of block u; scores of block u+1; P.V of
+    // block u-1.  At the two ends the neighbour slot is clamped: its product is unused
+    // (scores) or multiplied by zero probabilities (P.V).
+    auto unit = [&](floatx16& s_cur, floatx16& s_nxt, typename T::v8 (&p_prev)[2], typename T::v8 (&p_cur)[2], int u) {
+      const int un = u + 1 > b_hi - 1 ? b_hi - 1 : u + 1;
+      const int up = u - 1 < b_lo ? b_lo : u - 1;
+      const uint16_t* kblk = &lds_k[(un - b_lo) * kBlk];
+      const uint16_t* vblk = &lds_v[(up - b_lo) * kBlk];
+      typename T::v8 ka[4], va[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag_swz<T>(kblk, l32, hh, ks);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) va[i] = load_vt_frag_swz<T>(vblk, lane, i >> 1, i & 1);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s_nxt = T::mfma(ka[ks], qreg[0][ks], s_nxt);
+        st.oacc[0][ks & 1] = T::mfma(va[ks], p_prev[ks >> 1], st.oacc[0][ks & 1]);
+      }
+      // blocks every valid query of the wavefront sees completely need no mask work
+      const int kb0 = u * 32;
+      const bool interior = kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr;
+      uint32_t pk[8];
+      float blk;
+      uint32_t vis = 0xFFFFu;
+      if (interior) {
+        prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
+      } else {
+        vis = visible_bits(kb0, hh, jlo, jhi);
+        prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+      }
+      // !(blk <= limit) also catches a NaN sum; no reference yet = first visible block
+      const bool trig = alive && (!(blk <= kPLimit) || st.m_ref[0] == -INFINITY);
+      if (__any(trig)) {
+        // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
+        const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
+        float t0 = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+        const float tmax = max_xor32(t0);
+        rescale_rows<1>(st, 0, row_trig, tmax, c);
+        prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+      }
+      st.lsum[0] += blk;
+      p_cur[0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+      p_cur[1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
+    };
+    auto drain = [&](typename T::v8 (&p_last)[2], int u) {
+      const uint16_t* vblk = &lds_v[(u - b_lo) * kBlk];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        st.oacc[0][i & 1] = T::mfma(load_vt_frag_swz<T>(vblk, lane, i >> 1, i & 1), p_last[i >> 1], st.oacc[0][i & 1]);
+    };
+    int u = fb;
+    for (; u + 1 <= lb; u += 2) {
+      unit(sA, sB, pA, pB, u);
+      unit(sB, sA, pB, pA, u + 1);
+    }
+    if (u <= lb) {
+      unit(sA, sB, pA, pB, u);
+      drain(pB, u);
+    } else {
+      drain(pA, lb);
+    }
+  }
+  __syncthreads();  // all blocks consumed: the K storage becomes the epilogue patches
   epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
 }
 
@@ -807,26 +1030,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     // kPLimit, an infinity included, pushes it over).  Only then - rarely - is the exact
     // block maximum computed, the reference refreshed and the block redone.
     auto softmax_block = [&](const floatx16& sv, float mcq, uint32_t (&pk)[8], float& blk) {
-      const float nmc = -mcq;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-#ifdef FA_X_NOSOFTMAX
-        pk[r] = (__builtin_bit_cast(uint32_t, sv[2 * r]) & 0x3fff3fffu) ^ __builtin_bit_cast(uint32_t, sv[2 * r + 1] + nmc);
-#else
-        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r], c, nmc));
-        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r + 1], c, nmc));
-        pk[r] = T::pack2(e0, e1);
-#endif
-      }
-      // the row sum is taken over the ROUNDED probabilities, the same numbers the
-      // matrix product uses, two per instruction
-      float l0 = 0.f, l1 = 0.f;
-#pragma unroll
-      for (int r = 0; r < 8; r += 2) {
-        l0 = T::sum2(pk[r], l0);
-        l1 = T::sum2(pk[r + 1], l1);
-      }
-      blk = l0 + l1;
+      prob_block<T, false>(sv, c, mcq, 0xFFFFu, pk, blk);
     };
     // One unit.  QB: query block of the current scores; NQ: query block of the next
     // unit; PQ: query block of the previous unit; LOAD: this unit starts a new key block
@@ -838,17 +1042,10 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       constexpr int QB = decltype(QBc)::value, NQ = decltype(NQc)::value, PQ = decltype(PQc)::value;
       constexpr bool LOAD = decltype(LOADc)::value;
       if (LOAD) {
-#ifdef FA_X_NOLDS
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) ka[ks] = qreg[0][ks];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = qreg[0][i];
-#else
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) ka[ks] = k_frag(kblk, ks);
 #pragma unroll
         for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = vt_frag(vblk, i >> 1, i & 1);
-#endif
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
@@ -888,11 +1085,9 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       constexpr int STAGE = decltype(STAGEc)::value;
       const uint16_t* kt = &lds_k[STAGE * kBN * kD];
       const uint16_t* vt = &lds_v[STAGE * kBN * kD];
-#ifndef FA_X_NOFETCH
       // the stage being filled was last read in iteration t-1; every wavefront is past
       // that iteration's barrier
       if (t + 1 < nf) fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * kD], &lds_v[(STAGE ^ 1) * kBN * kD]);
-#endif
       if (wave_has_rows) {
         if constexpr (NQB == 1) {
           unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt);
@@ -904,12 +1099,8 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
           unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kD, vt + 32 * kD);
         }
       }
-#ifndef FA_X_NOFETCH
       wait_direct_loads();  // this wavefront's share of the next tile has landed
-#endif
-#ifndef FA_X_NOBARRIER
       __syncthreads();
-#endif
     };
     int t = 0;
     for (; t + 1 < nf; t += 2) {
@@ -988,7 +1179,11 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
-    hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
+    // 32-key blocks a 128-row query tile can touch (tiles start at multiples of 128)
+    const bool two_sided = a.wl >= 0 && a.wr >= 0;
+    const int blocks = two_sided ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+    if (blocks <= kResBlocks) hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
     if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
