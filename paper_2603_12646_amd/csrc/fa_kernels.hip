@@ -190,19 +190,30 @@ __device__ __forceinline__ typename T::v8 load_vt_frag_scalar(const uint16_t* vb
   return __builtin_bit_cast(typename T::v8, x);
 }
 
-// The same two operands from an UNPADDED, swizzled tile (64 halves per row), the layout
-// that direct global->LDS loads produce: 16-byte chunk position c' of row r holds logical
-// chunk c' ^ (r & 7) for K and c' ^ 2(r & 3) for V.  kblk / vblk must start at a row that
-// is a multiple of 8.
+// The same two operands from an UNPADDED, swizzled tile (64 halves = 128 bytes per row),
+// the layout that direct global->LDS loads produce: 16-byte chunk position c' of row r
+// holds logical chunk c' ^ k_swz(r) for K and c' ^ v_swz(r) for V.  LDS has 64 four-byte
+// banks, so two consecutive rows cover all banks once and the row's parity already picks
+// the half; the swizzles spread what remains.
+//   K: the 16-byte operand read of a k-step touches rows 0..15 at one chunk (lanes 0..15)
+//      and the neighbouring chunk of the same rows (lanes 32..47): rows of equal parity
+//      must land on 8 different chunk positions, whichever 16 lanes are served together.
+//   V: a transpose read touches 4 rows x 4 chunks (or 8 rows x 2 chunks) per 32 lanes.
+// Measured on gfx950: 246 B/clk per CU for the K reads and 199 B/clk for the V reads,
+// the same as conflict-free linear addresses.  kblk / vblk must start at a row that is a
+// multiple of 16.
+__device__ __forceinline__ int k_swz(int r) { return 2 * ((r >> 1) & 3) + ((r >> 3) & 1); }
+__device__ __forceinline__ int v_swz(int r) { return 4 * ((r >> 1) & 1) + 2 * ((r >> 2) & 1); }
+
 template <class T>
 __device__ __forceinline__ typename T::v8 load_k_frag_swz(const uint16_t* kblk, int l32, int hh, int ks) {
-  return as_v8<T>(*(const uint4*)&kblk[l32 * kD + (((2 * ks + hh) ^ (l32 & 7)) * 8)]);
+  return as_v8<T>(*(const uint4*)&kblk[l32 * kD + (((2 * ks + hh) ^ k_swz(l32)) * 8)]);
 }
 template <class T>
 __device__ __forceinline__ typename T::v8 load_vt_frag_swz(const uint16_t* vblk, int lane, int ks2, int db) {
   const int hh = lane >> 5, p16 = lane & 15, g = (lane >> 4) & 1;
   const int row = ks2 * 16 + 4 * hh + (p16 >> 2);
-  const int off = (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ (2 * (p16 >> 2))) * 8) + (p16 & 1) * 4;
+  const int off = (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ v_swz(row)) * 8) + (p16 & 1) * 4;
   typedef __attribute__((address_space(3))) shortx4 lds_s4;
   const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * kD + off]);
   const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * kD + off]);
@@ -641,8 +652,8 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
   // tensor (rows >= n are masked or zeroed below), so its global offset is a per-lane
   // 32-bit byte offset from the (batch, head) slice.
   const int dl_r = 8 * wave + (lane >> 3);
-  const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ (lane >> 3)) * 8);
-  const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8);
+  const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ k_swz(dl_r)) * 8);
+  const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ v_swz(dl_r)) * 8);
   const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
   auto issue_block = [&](int t) {
     const int stage = t % kWinStages;
@@ -759,8 +770,8 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   // below), so its global offset is a per-lane 32-bit byte offset from the slice.
   const int dl_r = 8 * wave + (lane >> 3);
   {
-    const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ (lane >> 3)) * 8);
-    const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8);
+    const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ k_swz(dl_r)) * 8);
+    const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ v_swz(dl_r)) * 8);
     const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
 #pragma unroll
     for (int i = 0; i < kResBlocks; ++i) {
@@ -939,15 +950,13 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // a wavefront's load fills 1 KB of LDS in lane order, i.e. 8 rows of 128 bytes, so the
   // LDS tile is unpadded [64 rows][8 chunks of 16 bytes] and bank conflicts are avoided by
   // choosing WHICH global chunk each lane fetches: chunk position c' of row r holds global
-  // chunk c' ^ (r & 7) for K (the 16-byte operand reads of 8 consecutive rows then hit 8
-  // different chunk positions) and c' ^ 2(r & 3) for V (the four rows x two chunks of a
-  // transpose read hit 8 different positions).  Wavefront w moves rows 8w..8w+7 of each
+  // chunk c' ^ k_swz(r) for K and c' ^ v_swz(r) for V.  Wavefront w moves rows 8w..8w+7 of each
   // 32-row half.  Row bases are wavefront-uniform; each lane adds a fixed offset.  Halves
   // whose rows would leave [0, N) are only ever the unused ends of the pipeline (V before
   // block 0, K after the last full block): their base is clamped, their contents unused.
   const int dl_r = 8 * wave + (lane >> 3);  // row within a 32-row half
-  const uint32_t koff = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane & 7) ^ (lane >> 3)) * 8));  // bytes
-  const uint32_t voff = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8));
+  const uint32_t koff = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane & 7) ^ k_swz(dl_r)) * 8));  // bytes
+  const uint32_t voff = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane & 7) ^ v_swz(dl_r)) * 8));
   auto fetch = [&](int t, uint16_t* kstage, uint16_t* vstage) {
     const int k0r = t * kBN + 32 < 0 ? 0 : t * kBN + 32;
     const int k1r = t * kBN + 64 > N - 32 ? N - 32 : t * kBN + 64;
@@ -983,12 +992,13 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // per-lane fragment offsets (16-bit elements) into a 32-row block of a swizzled tile
   uint32_t kfo[4], vfo[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) kfo[ks] = l32 * kD + (((2 * ks + hh) ^ (l32 & 7)) * 8);
+  for (int ks = 0; ks < 4; ++ks) kfo[ks] = l32 * kD + (((2 * ks + hh) ^ k_swz(l32)) * 8);
   {
     const int p16 = lane & 15, g = (lane >> 4) & 1;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
-      vfo[db] = (4 * hh + (p16 >> 2)) * kD + (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ (2 * (p16 >> 2))) * 8) +
+      vfo[db] = (4 * hh + (p16 >> 2)) * kD +
+                (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ v_swz(4 * hh + (p16 >> 2))) * 8) +
                 (p16 & 1) * 4;
   }
   auto k_frag = [&](const uint16_t* kblk, int ks) { return as_v8<T>(*(const uint4*)&kblk[kfo[ks]]); };
