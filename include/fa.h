@@ -64,7 +64,7 @@ enum {
   FA_OK = 0,
   FA_ERR_NULL_POINTER = -1,  /* q, k, v or o is NULL (or params is NULL)               */
   FA_ERR_BAD_SHAPE = -2,     /* batch, heads or max_len <= 0, or too large for a grid  */
-  FA_ERR_BAD_HEAD_DIM = -3,  /* head_dim not in the supported set {64}                 */
+  FA_ERR_BAD_HEAD_DIM = -3,  /* head_dim not in the supported set {32, 64, 128}        */
   FA_ERR_BAD_SCALE = -4,     /* scale is NaN or infinite (0 and negatives are legal)   */
   FA_ERR_BAD_WINDOW = -5,    /* window == 0 (fa_fwd); window_left/right inconsistent   */
   FA_ERR_MISALIGNED = -6,    /* a tensor pointer is not 16-byte aligned, or a stride
@@ -80,7 +80,8 @@ enum { FA_DTYPE_F16 = 0, FA_DTYPE_BF16 = 1 };
  * fa_fwd: fp16 attention forward (the paper's kernel is fp16, Sec. 4.1.3 "HIP Kernel
  * and ORT Registration").
  *
- *   batch, heads, max_len, head_dim : tensor extents; head_dim must be 64.
+ *   batch, heads, max_len, head_dim : tensor extents; head_dim is 32, 64 or 128 (the
+ *            paper's operator dispatches on these three at run time, Sec. 4.1.3).
  *   scale  : multiplies q.k before the softmax (the operator's `scale` attribute;
  *            1/sqrt(head_dim) in the paper's models).  Applied in fp32 to the
  *            fp32-accumulated dot product.
@@ -136,7 +137,7 @@ typedef struct fa_params {
    bits 8-11 workgroup-to-tile mapping. */
 #define FA_TUNE_BM_AUTO 0x0u
 #define FA_TUNE_BM_128 0x1u  /* 4 wavefronts x 32 query rows  */
-#define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows  */
+#define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows (head_dim 64 only; ignored otherwise) */
 #define FA_TUNE_V_AUTO 0x00u
 #define FA_TUNE_V_LDS_TRANSPOSE 0x10u /* ds_read_b64_tr_b16 operand loads */
 #define FA_TUNE_V_SCALAR 0x20u        /* 16-bit LDS reads (slow reference path) */

@@ -59,7 +59,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->dtype != FA_DTYPE_F16 && p->dtype != FA_DTYPE_BF16) return FA_ERR_BAD_DTYPE;
   if (!p->q || !p->k || !p->v || !p->o) return FA_ERR_NULL_POINTER;
   if (p->batch <= 0 || p->heads <= 0 || p->max_len <= 0) return FA_ERR_BAD_SHAPE;
-  if (p->head_dim != 64) return FA_ERR_BAD_HEAD_DIM;
+  if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128) return FA_ERR_BAD_HEAD_DIM;
   if (!std::isfinite(p->scale)) return FA_ERR_BAD_SCALE;
   if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->o))
     return FA_ERR_MISALIGNED;
@@ -77,7 +77,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->v_strides, a.vs, p->heads, p->max_len, p->head_dim))) return rc;
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
 
-  const int bm = t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p));
+  // head_dim 32 and 128 run the 128-row kernel only (the tile-size hint is ignored there)
+  const int bm = p->head_dim != 64 ? 128
+                                   : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
   const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
   const int64_t total = n_qtiles * p->batch * p->heads;
   // element count and grid must stay inside what the kernels index with
@@ -85,7 +87,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (elems > 9.0e18L || total > 0x7FFFFFF0LL || p->max_len > (1 << 30)) return FA_ERR_BAD_SHAPE;
 
   a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o; a.lse = p->lse; a.seq_lens = p->seq_lens;
-  a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len;
+  a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len; a.head_dim = p->head_dim;
   const float c = std::fabs(p->scale) * kLog2e;
   a.c = c;
   a.negate_q = std::signbit(p->scale) && p->scale != 0.0f ? 1 : 0;

@@ -10,6 +10,7 @@ struct FaKernelArgs {
   float* lse;               // may be null
   const int32_t* seq_lens;  // device, may be null
   int32_t batch, heads, max_len;
+  int32_t head_dim;         // 32, 64 or 128
   int64_t qs[3], ks[3], vs[3], os[3];  // element strides: batch, head, row
   float c;          // |scale| * log2(e): scores are handled in the log2 domain
   int32_t negate_q; // scale < 0: q's sign bits are flipped on load, c stays positive

@@ -63,15 +63,18 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef short shortx8 __attribute__((ext_vector_type(8)));
 
-constexpr int kD = 64;        // head_dim
+constexpr int kD = 64;        // head_dim of the pipelined kernels (the masked kernel takes 32, 64, 128)
 constexpr int kBN = 64;       // keys per LDS tile
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-// LDS row strides in 16-bit elements.  K is read with 16-byte accesses by 32 rows at
-// once (row stride 36 dwords puts 8 consecutive rows on disjoint banks); V is read by
-// the transpose load, 4 rows x 32 bytes per 16 lanes (row stride 40 dwords).
-constexpr int kSK = kD + 8;
-constexpr int kSV = kD + 16;
+// Row strides of the PADDED LDS tiles in 16-bit elements, for head_dim D.  K is read with
+// 16-byte accesses by 32 rows at once (a row stride of D/2 + 4 dwords puts 16 consecutive
+// rows on 16 different 16-byte bank groups for D = 32, 64, 128); V is read by the
+// transpose load, 4 rows x 32 bytes per 16 lanes.
+constexpr int stride_k(int D) { return D + 8; }
+constexpr int stride_v(int D) { return D + 16; }
+constexpr int kSK = stride_k(kD);
+constexpr int kSV = stride_v(kD);
 constexpr float kLn2 = 0.693147180559945309f;
 // A lane's 16 probabilities of one block may sum to at most this (against the row's
 // current reference) before the reference is refreshed.  2^14 keeps every single p
@@ -154,23 +157,24 @@ __device__ __forceinline__ typename T::v8 as_v8(uint4 u) {
 }
 
 // A operand of S^T = K Q^T for one k-step: K[row l%32][16*ks + 8*(l/32) .. +7]
-template <class T>
+template <class T, int D = kD>
 __device__ __forceinline__ typename T::v8 load_k_frag(const uint16_t* kblk, int l32, int hh, int ks) {
-  return as_v8<T>(*(const uint4*)&kblk[l32 * kSK + ks * 16 + hh * 8]);
+  return as_v8<T>(*(const uint4*)&kblk[l32 * stride_k(D) + ks * 16 + hh * 8]);
 }
 
 // A operand of O^T = V^T P^T: column d = 32*db + l%32 of V, summation slots
 // (hh, e) = keys 16*ks2 + (e < 4 ? 4*hh + e : 8 + 4*hh + e - 4) of the 32-key block.
 // Within 16 lanes, lane p fetches 4 consecutive d of key row p/4; the transpose
 // read hands lane i the 4 keys of column i.
-template <class T>
+template <class T, int D = kD>
 __device__ __forceinline__ typename T::v8 load_vt_frag(const uint16_t* vblk, int lane, int ks2, int db) {
+  constexpr int SV = stride_v(D);
   const int hh = lane >> 5, p16 = lane & 15;
   const int row = ks2 * 16 + 4 * hh + (p16 >> 2);
   const int col = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
   typedef __attribute__((address_space(3))) shortx4 lds_s4;
-  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * kSV + col]);
-  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * kSV + col]);
+  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * SV + col]);
+  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * SV + col]);
   shortx8 x;
   x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
   x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
@@ -178,14 +182,14 @@ __device__ __forceinline__ typename T::v8 load_vt_frag(const uint16_t* vblk, int
 }
 
 // Same operand through plain 16-bit LDS reads (slow; kept as an independent path).
-template <class T>
+template <class T, int D = kD>
 __device__ __forceinline__ typename T::v8 load_vt_frag_scalar(const uint16_t* vblk, int lane, int ks2, int db) {
   const int hh = lane >> 5, l32 = lane & 31;
   shortx8 x;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int row = ks2 * 16 + (e < 4 ? 4 * hh + e : 8 + 4 * hh + e - 4);
-    x[e] = (short)vblk[row * kSV + db * 32 + l32];
+    x[e] = (short)vblk[row * stride_v(D) + db * 32 + l32];
   }
   return __builtin_bit_cast(typename T::v8, x);
 }
@@ -223,9 +227,9 @@ __device__ __forceinline__ typename T::v8 load_vt_frag_swz(const uint16_t* vblk,
   return __builtin_bit_cast(typename T::v8, x);
 }
 
-template <int NQB>
+template <int NQB, int D = kD>
 struct RowState {
-  floatx16 oacc[NQB][2];  // O^T: [qb][d block], rows d = 32*db + 8*(r/4) + 4*hh + r%4
+  floatx16 oacc[NQB][D / 32];  // O^T: [qb][d block], rows d = 32*db + 8*(r/4) + 4*hh + r%4
   float m_ref[NQB];       // reference maximum (raw score units), -inf before the first key
   float mc[NQB];          // m_ref * c, 0 while m_ref = -inf
   float lsum[NQB];        // this lane's share of the row sum
@@ -234,8 +238,8 @@ struct RowState {
 // Refresh the reference of rows whose block maximum ran away from it.  Each lane
 // decides on its own row's evidence only, so a row's arithmetic never depends on
 // which other rows share its wavefront.
-template <int NQB>
-__device__ __forceinline__ void rescale_rows(RowState<NQB>& st, int qb, bool refresh, float tmax, float c) {
+template <int NQB, int D>
+__device__ __forceinline__ void rescale_rows(RowState<NQB, D>& st, int qb, bool refresh, float tmax, float c) {
   const float m_new = refresh ? tmax : st.m_ref[qb];
   const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * c;
   // nothing has been accumulated while the old reference is -inf: keep 0 * alpha out of
@@ -245,7 +249,7 @@ __device__ __forceinline__ void rescale_rows(RowState<NQB>& st, int qb, bool ref
   st.mc[qb] = mc_new;
   st.lsum[qb] *= alpha;
 #pragma unroll
-  for (int db = 0; db < 2; ++db)
+  for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha;
 }
@@ -301,8 +305,8 @@ __device__ __forceinline__ uint32_t visible_bits(int kb0, int hh, int jlo, int j
 // is the visible key range of the lane's query.  FRAG selects how operands come out of
 // LDS: 0 padded tile + transpose read, 1 padded tile + 16-bit reads, 2 swizzled tile +
 // transpose read.
-template <class T, int NQB, bool MASKED, int FRAG>
-__device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T::v8 (&qreg)[NQB][4],
+template <class T, int NQB, bool MASKED, int FRAG, int D>
+__device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typename T::v8 (&qreg)[NQB][D / 16],
                                              const uint16_t* kblk, const uint16_t* vblk, int kb0,
                                              const int (&jlo)[NQB], const int (&jhi)[NQB], int lane,
                                              float c, float tau_raw) {
@@ -312,9 +316,10 @@ __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T
   for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
+  static_assert(FRAG != 2 || D == kD, "swizzled tiles exist for head_dim 64 only");
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    const typename T::v8 ka = FRAG == 2 ? load_k_frag_swz<T>(kblk, l32, hh, ks) : load_k_frag<T>(kblk, l32, hh, ks);
+  for (int ks = 0; ks < D / 16; ++ks) {
+    const typename T::v8 ka = FRAG == 2 ? load_k_frag_swz<T>(kblk, l32, hh, ks) : load_k_frag<T, D>(kblk, l32, hh, ks);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) sacc[qb] = T::mfma(ka, qreg[qb][ks], sacc[qb]);
   }
@@ -338,7 +343,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T
     }
     tmax = max_xor32(tmax);
     const bool refresh = (tmax - st.m_ref[qb]) > tau_raw;
-    if (__any(refresh)) rescale_rows<NQB>(st, qb, refresh, tmax, c);
+    if (__any(refresh)) rescale_rows(st, qb, refresh, tmax, c);
     const float nmc = -st.mc[qb];
     float p[16];
     float ls = st.lsum[qb];
@@ -356,10 +361,10 @@ __device__ __forceinline__ void simple_block(RowState<NQB>& st, const typename T
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2) {
 #pragma unroll
-    for (int db = 0; db < 2; ++db) {
+    for (int db = 0; db < D / 32; ++db) {
       const typename T::v8 va = FRAG == 2   ? load_vt_frag_swz<T>(vblk, lane, ks2, db)
-                                : FRAG == 0 ? load_vt_frag<T>(vblk, lane, ks2, db)
-                                            : load_vt_frag_scalar<T>(vblk, lane, ks2, db);
+                                : FRAG == 0 ? load_vt_frag<T, D>(vblk, lane, ks2, db)
+                                            : load_vt_frag_scalar<T, D>(vblk, lane, ks2, db);
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         const uint4 pu = make_uint4(pk[qb][ks2 * 4 + 0], pk[qb][ks2 * 4 + 1], pk[qb][ks2 * 4 + 2],
@@ -408,19 +413,20 @@ __device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc
 }
 
 // Workgroup entirely in the padding: o = 0, lse = -inf.
-template <int BM>
+template <int BM, int D = kD>
 __device__ __forceinline__ void zero_fill(const FaKernelArgs& a, const TileCoord& tc, uint16_t* op, float* lsep) {
   const int tid = threadIdx.x, N = a.max_len;
-  const int r = tid >> 3, c16 = tid & 7;
-  for (int row = tc.q0 + r; row < tc.q0 + BM && row < N; row += 32)
+  constexpr int CH = D / 8;  // 16-byte chunks per row
+  const int r = tid / CH, c16 = tid % CH;
+  for (int row = tc.q0 + r; row < tc.q0 + BM && row < N; row += kThreads / CH)
     *(uint4*)(op + row * a.os[2] + c16 * 8) = make_uint4(0, 0, 0, 0);
   if (lsep)
     for (int row = tc.q0 + tid; row < tc.q0 + BM && row < N; row += kThreads) lsep[row] = -INFINITY;
 }
 
-template <class T, int NQB>
+template <class T, int NQB, int KS>
 __device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp, int qw0, int lane,
-                                       typename T::v8 (&qreg)[NQB][4]) {
+                                       typename T::v8 (&qreg)[NQB][KS]) {
   const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -428,7 +434,7 @@ __device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp
     row = row < N ? row : N - 1;
     const uint16_t* src = qp + row * a.qs[2] + hh * 8;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       uint4 u = *(const uint4*)(src + ks * 16);
       if (a.negate_q) {
         u.x ^= 0x80008000u; u.y ^= 0x80008000u; u.z ^= 0x80008000u; u.w ^= 0x80008000u;
@@ -438,15 +444,15 @@ __device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp
   }
 }
 
-template <int NQB>
-__device__ __forceinline__ void init_state(RowState<NQB>& st) {
+template <int NQB, int D>
+__device__ __forceinline__ void init_state(RowState<NQB, D>& st) {
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     st.m_ref[qb] = -INFINITY;
     st.mc[qb] = 0.f;
     st.lsum[qb] = 0.f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] = 0.f;
   }
@@ -455,15 +461,19 @@ __device__ __forceinline__ void init_state(RowState<NQB>& st) {
 // Epilogue: o = O / l, cast, store; lse.  A lane holds one output ROW in pieces of four
 // columns, so storing from registers would scatter 8-byte pieces over 32 rows per
 // instruction.  Each wavefront instead transposes its 32 x 64 block through a private
-// LDS patch (rows padded to 144 bytes) and stores whole 128-byte rows, 16 bytes per lane.
-// wave_patch: kEpiPatch 16-bit elements of LDS owned by this wavefront; the caller has
+// LDS patch (rows padded by 16 bytes) and stores whole rows, 16 bytes per lane.
+// wave_patch: epi_patch(D) 16-bit elements of LDS owned by this wavefront; the caller has
 // made sure (barrier) that nobody still reads tiles from that memory.
-constexpr int kEpiStride = kD + 8;
-constexpr int kEpiPatch = 32 * kEpiStride;
+constexpr int epi_stride(int D) { return D + 8; }
+constexpr int epi_patch(int D) { return 32 * epi_stride(D); }
+constexpr int kEpiPatch = epi_patch(kD);
 
-template <class T, int NQB>
-__device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& st, uint16_t* op, float* lsep,
+template <class T, int NQB, int D>
+__device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB, D>& st, uint16_t* op, float* lsep,
                                          int qw0, int n, int lane, uint16_t* wave_patch) {
+  constexpr int kEpiStride = epi_stride(D);
+  constexpr int CH = D / 8;         // 16-byte chunks per output row
+  constexpr int RPP = 64 / CH;      // rows stored per pass
   const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -472,7 +482,7 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& s
     const bool live = (ig < n) && (ltot > 0.f);
     const float inv = live ? 1.0f / ltot : 0.f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db) {
+    for (int db = 0; db < D / 32; ++db) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
@@ -484,11 +494,11 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& s
     }
     // same wavefront writes and reads the patch: program order is enough
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-      const int r = pass * 8 + (lane >> 3);
-      const uint4 v = *(const uint4*)&wave_patch[r * kEpiStride + (lane & 7) * 8];
+    for (int pass = 0; pass < 32 / RPP; ++pass) {
+      const int r = pass * RPP + lane / CH;
+      const uint4 v = *(const uint4*)&wave_patch[r * kEpiStride + (lane % CH) * 8];
       const int row = qw0 + qb * 32 + r;
-      if (row < N) *(uint4*)(op + row * a.os[2] + (lane & 7) * 8) = v;
+      if (row < N) *(uint4*)(op + row * a.os[2] + (lane % CH) * 8) = v;
     }
     if (lsep && hh == 0 && ig < N)
       lsep[ig] = live ? (st.mc[qb] + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
@@ -498,11 +508,13 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB>& s
 // ======================================================================================
 // Masked kernel: windows (and any tile that needs per-element masks)
 // ======================================================================================
-template <class T, int NQB, bool V_TR>
+template <class T, int D, int NQB, bool V_TR>
 __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32 * NQB;
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kBN * kSK];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kBN * kSV];
+  constexpr int SK = stride_k(D), SV = stride_v(D);
+  static_assert(2 * kBN * SK >= kWaves * epi_patch(D), "the K stages double as the epilogue patches");
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kBN * SK];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kBN * SV];
 
   TileCoord tc;
   if (!locate_tile<BM>(a, tc)) return;
@@ -519,7 +531,7 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
   float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
 
   if (q0 >= n) {
-    zero_fill<BM>(a, tc, op, lsep);
+    zero_fill<BM, D>(a, tc, op, lsep);
     return;
   }
 
@@ -536,10 +548,10 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
   const int qw_last = (qw0 + 32 * NQB < n ? qw0 + 32 * NQB : n) - 1;  // < qw0: all padding
   const bool wave_has_rows = qw_last >= qw0;
 
-  typename T::v8 qreg[NQB][4];
+  typename T::v8 qreg[NQB][D / 16];
   load_q<T, NQB>(a, qp, qw0, lane, qreg);
-  RowState<NQB> st;
-  init_state<NQB>(st);
+  RowState<NQB, D> st;
+  init_state(st);
   int jlo[NQB], jhi[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -550,10 +562,12 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
     if (a.wr >= 0 && ig + a.wr < jhi[qb]) jhi[qb] = ig + a.wr;
   }
 
-  // staging: thread t moves 16 bytes of rows t/8 and t/8 + 32 (named registers, not an
-  // array: an array captured by the lambdas ends up in scratch memory)
-  const int st_r = tid >> 3, st_c = (tid & 7) * 8;
-  uint4 kst0, kst1, vst0, vst1;
+  // staging: a 64-key tile is 64 rows of D/8 16-byte chunks; thread t moves chunk t % (D/8)
+  // of rows t / (D/8) + i * RS, i = 0 .. NST-1 (named registers, not an array: an array
+  // captured by the lambdas ends up in scratch memory)
+  constexpr int CH = D / 8, RS = kThreads / CH, NST = kBN / RS;  // NST = 1, 2, 4 for D = 32, 64, 128
+  const int st_r = tid / CH, st_c = (tid % CH) * 8;
+  uint4 kst0, kst1, kst2, kst3, vst0, vst1, vst2, vst3;
   auto fetch_row = [&](int jg, uint4& kk, uint4& vv) {
     const int jc = jg < N ? jg : N - 1;
     kk = *(const uint4*)(kp + jc * a.ks[2] + st_c);
@@ -563,13 +577,25 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
   };
   auto fetch = [&](int t) {
     fetch_row(t * kBN + st_r, kst0, vst0);
-    fetch_row(t * kBN + 32 + st_r, kst1, vst1);
+    if (NST > 1) fetch_row(t * kBN + RS + st_r, kst1, vst1);
+    if (NST > 2) {
+      fetch_row(t * kBN + 2 * RS + st_r, kst2, vst2);
+      fetch_row(t * kBN + 3 * RS + st_r, kst3, vst3);
+    }
   };
   auto stash = [&](int buf) {
-    *(uint4*)&lds_k[buf][st_r * kSK + st_c] = kst0;
-    *(uint4*)&lds_k[buf][(32 + st_r) * kSK + st_c] = kst1;
-    *(uint4*)&lds_v[buf][st_r * kSV + st_c] = vst0;
-    *(uint4*)&lds_v[buf][(32 + st_r) * kSV + st_c] = vst1;
+    *(uint4*)&lds_k[buf][st_r * SK + st_c] = kst0;
+    *(uint4*)&lds_v[buf][st_r * SV + st_c] = vst0;
+    if (NST > 1) {
+      *(uint4*)&lds_k[buf][(RS + st_r) * SK + st_c] = kst1;
+      *(uint4*)&lds_v[buf][(RS + st_r) * SV + st_c] = vst1;
+    }
+    if (NST > 2) {
+      *(uint4*)&lds_k[buf][(2 * RS + st_r) * SK + st_c] = kst2;
+      *(uint4*)&lds_v[buf][(2 * RS + st_r) * SV + st_c] = vst2;
+      *(uint4*)&lds_k[buf][(3 * RS + st_r) * SK + st_c] = kst3;
+      *(uint4*)&lds_v[buf][(3 * RS + st_r) * SV + st_c] = vst3;
+    }
   };
 
   fetch(t_lo);
@@ -587,8 +613,8 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
         if (kb0 >= n) continue;
         if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
         if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
-        simple_block<T, NQB, true, V_TR ? 0 : 1>(st, qreg, &lds_k[buf][kb * 32 * kSK], &lds_v[buf][kb * 32 * kSV],
-                                         kb0, jlo, jhi, lane, a.c, a.tau_raw);
+        simple_block<T, NQB, true, V_TR ? 0 : 1>(st, qreg, &lds_k[buf][kb * 32 * SK], &lds_v[buf][kb * 32 * SV],
+                                                 kb0, jlo, jhi, lane, a.c, a.tau_raw);
       }
     }
     if (t + 1 < t_hi) stash(buf ^ 1);
@@ -596,7 +622,7 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
     buf ^= 1;
   }
   // the loop ended with a barrier: the K stages are free
-  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, &lds_k[0][0] + wave * kEpiPatch);
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, &lds_k[0][0] + wave * epi_patch(D));
 }
 
 // ======================================================================================
@@ -681,7 +707,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
   typename T::v8 qreg[1][4];
   load_q<T, 1>(a, qp, qw0, lane, qreg);
   RowState<1> st;
-  init_state<1>(st);
+  init_state(st);
   int jlo[1], jhi[1];
   {
     const int ig = qw0 + l32;
@@ -790,7 +816,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   typename T::v8 qreg[1][4];
   load_q<T, 1>(a, qp, qw0, lane, qreg);
   RowState<1> st;
-  init_state<1>(st);
+  init_state(st);
   const int ig = qw0 + l32;
   const bool alive = ig < n;
   int jlo = ig - a.wl > 0 ? ig - a.wl : 0;
@@ -863,7 +889,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 #pragma unroll
         for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
         const float tmax = max_xor32(t0);
-        rescale_rows<1>(st, 0, row_trig, tmax, c);
+        rescale_rows(st, 0, row_trig, tmax, c);
         prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
       }
       st.lsum[0] += blk;
@@ -930,7 +956,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   typename T::v8 qreg[NQB][4];
   load_q<T, NQB>(a, qp, qw0, lane, qreg);
   RowState<NQB> st;
-  init_state<NQB>(st);
+  init_state(st);
 
   const int nf = n / kBN;  // full tiles: every key visible to every valid query
   const float c = a.c, tau_raw = a.tau_raw;
@@ -1079,7 +1105,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s_cur[r]), s_cur[r + 1]);
         const float tmax = max_xor32(t0);
         // the accumulator of this query block already holds P.V of all earlier key blocks
-        rescale_rows<NQB>(st, QB, row_trig, tmax, c);
+        rescale_rows(st, QB, row_trig, tmax, c);
         softmax_block(s_cur, st.mc[QB], pk, blk);
       }
       st.lsum[QB] += blk;
@@ -1185,7 +1211,16 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
-  if (global && v_path == 0) {
+  if (a.head_dim != kD) {
+    // head_dim 32 / 128: the masked kernel covers every mask; bm is 128 here
+    if (a.head_dim == 32) {
+      if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true>), dim3(grid), block, 0, s, a);
+      else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, false>), dim3(grid), block, 0, s, a);
+    } else {
+      if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true>), dim3(grid), block, 0, s, a);
+      else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, false>), dim3(grid), block, 0, s, a);
+    }
+  } else if (global && v_path == 0) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
@@ -1195,11 +1230,11 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
     if (blocks <= kResBlocks) hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 2, false>), dim3(grid), block, 0, s, a);
+    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 2, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 2, false>), dim3(grid), block, 0, s, a);
   } else {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 1, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 1, false>), dim3(grid), block, 0, s, a);
+    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, false>), dim3(grid), block, 0, s, a);
   }
   return (int)hipGetLastError();
 }

@@ -188,10 +188,90 @@ def test_valid_call_returns_zero_and_bad_call_leaves_output_untouched():
     torch.cuda.synchronize()
     assert torch.isfinite(o).all()
     o2 = poison((B, H, N, D), "fp16")
-    assert fa.fa_fwd(qd, kd, vd, o2, None, B, H, None, N, 32, 0.125, -1, check=False) == -3
+    assert fa.fa_fwd(qd, kd, vd, o2, None, B, H, None, N, 48, 0.125, -1, check=False) == -3
     assert fa.fa_fwd(qd, kd, vd, o2, None, B, H, None, N, D, 0.125, 0, check=False) == -5
     torch.cuda.synchronize()
     assert torch.isnan(o2).all()
+
+
+# ------------------------------------------------------------------ head_dim 32 and 128
+HD_TUNINGS = {"auto": 0, "scalar_linear": fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_LINEAR,
+              "bm256_hint_ignored": fa.FA_TUNE_BM_256}
+
+
+@pytest.mark.parametrize("tuning", sorted(HD_TUNINGS))
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("D", [32, 128])
+@pytest.mark.parametrize("left,right", [(-1, -1), (63, 64), (0, 0), (0, 5), (70, -1), (-1, 9)])
+def test_head_dims_small_ragged_all_windows(D, dtype, left, right, tuning):
+    """The operator's other two head sizes (paper Sec. 4.1.3 dispatches on 32, 64, 128):
+    several key tiles, a ragged tail, padding inside a tile, a fully padded query tile."""
+    B, H, N = 2, 2, 333
+    _, q, k, v = draw(400 + D, B, H, N, D, dtype)
+    lens = [333, 120]
+    scale = 1.0 / np.sqrt(D)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, left, right)
+    o, lse = run_ex(q, k, v, lens, dtype, scale, left, right, HD_TUNINGS[tuning])
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"D={D} {dtype} {left},{right} {tuning}")
+
+
+@pytest.mark.parametrize("D", [32, 128])
+@pytest.mark.parametrize("N", [1, 31, 33, 64, 65, 129, 257])
+def test_head_dims_lengths_around_tile_edges(D, N):
+    B, H = 1, 2
+    for dtype in ("fp16", "bf16"):
+        _, q, k, v = draw(500 + N + D, B, H, N, D, dtype)
+        for window in (-1, 128, 2):
+            L, R = window_from_width(window)
+            o_ref, lse_ref = attention_oracle(q, k, v, None, 0.2, L, R)
+            o, lse = run_simple(q, k, v, None, dtype, 0.2, window)
+            check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"D={D} N={N} w={window}")
+
+
+@pytest.mark.parametrize("D", [32, 128])
+def test_head_dims_closed_forms_and_padding(D):
+    """Q = 0: o = mean of the visible V rows and lse = ln(#visible) exactly as counted from
+    the window and the length; garbage (NaN, Inf) in the padded rows changes nothing."""
+    B, H, N = 2, 2, 200
+    _, q, k, v = draw(600 + D, B, H, N, D, "fp16")
+    lens = [200, 77]
+    q0 = np.zeros_like(q)
+    o, lse = run_simple(q0, k, v, lens, "fp16", 0.125, 128)
+    for b, n in enumerate(lens):
+        for i in (0, 1, 63, 64, n // 2, n - 1):
+            lo, hi = max(0, i - 63), min(n - 1, i + 64)
+            assert abs(lse[b, 0, i] - np.log(hi - lo + 1)) <= 1e-3
+            assert np.abs(o[b, 1, i] - v[b, 1, lo:hi + 1].astype(np.float64).mean(axis=0)).max() <= 2e-3
+    o1, lse1 = run_simple(q, k, v, lens, "fp16", 0.125, -1)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for x, val in ((q2, np.nan), (k2, np.inf), (v2, np.nan)):
+        x[1, :, 77:] = val
+    o2, lse2 = run_simple(q2, k2, v2, lens, "fp16", 0.125, -1)
+    assert np.array_equal(o1, o2) and np.array_equal(lse1, lse2)
+
+
+@pytest.mark.parametrize("D", [32, 128])
+def test_head_dims_longer_sequence_sampled_rows(D):
+    """2K tokens, two lengths, global and local: sampled rows against the oracle."""
+    B, H, N = 2, 4, 2048
+    lens = [2048, 1500]
+    # peaked scores (gain 1.5) for the global fp16 leg as in the 8K workload; unit gain for the
+    # bf16 local leg as in the 32K workload (a peaked softmax over a few keys, rounded to 8
+    # mantissa bits before the second product, sits right at the 1e-2 bound)
+    for dtype, window, gain in (("fp16", -1, 1.5), ("bf16", 128, 1.0)):
+        _, q, k, v = draw(700 + D, B, H, N, D, dtype, qk_gain=gain)
+        scale = 1.0 / np.sqrt(D)
+        o, lse = run_simple(q, k, v, lens, dtype, scale, window)
+        L, R = window_from_width(window)
+        rows = np.array([0, 1, 63, 64, 127, 128, 777, 1499, 1500, 2047])
+        for b in range(B):
+            n = lens[b]
+            rr = rows[rows < n]
+            for h in (0, H - 1):
+                o_ref, lse_ref = attention_oracle_rows(q, k, v, b, h, rr, n, scale, L, R)
+                assert np.abs(o[b, h, rr] - o_ref).max() <= TOL[dtype]["max_abs"]
+                assert np.abs(lse[b, h, rr] - lse_ref).max() <= LSE_TOL
+            assert np.all(o[b, :, n:] == 0) and np.all(np.isneginf(lse[b, :, n:]))
 
 
 # ------------------------------------------------------------------ the five named workloads
