@@ -165,7 +165,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from workloads import CONFIGS, make_inputs
+    from workloads import ALL_CONFIGS, make_inputs
     import paper_2603_12646_amd as fa
 
     if not torch.cuda.is_available():
@@ -174,7 +174,7 @@ def main():
     fa.load_library()
     torch.cuda.set_device(0)
 
-    w = CONFIGS[args.workload]
+    w = ALL_CONFIGS[args.workload]
     lens, q, k, v = make_inputs(w)
     flops, nbytes = algorithmic_work(w, lens)
     wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup, args.tuning)
@@ -218,7 +218,7 @@ def main():
 
     if not args.no_others:
         others = {}
-        for name, ow in CONFIGS.items():
+        for name, ow in ALL_CONFIGS.items():
             if name == w.name:
                 continue
             ol, oq, ok_, ov = make_inputs(ow)
@@ -227,7 +227,7 @@ def main():
             wms, ems = gpu_time(ow, ol, oq, ok_, ov, steps, max(3, min(args.warmup, 10)), args.tuning)
             others[name] = {"ms_per_call": ems, "tflops": of / (ems * 1e-3) / 1e12,
                             "frac_mfma_peak": of / (ems * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
-                            "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype}
+                            "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype, "head_dim": ow.head_dim}
             del oq, ok_, ov
         out["config"]["other_workloads"] = others
 

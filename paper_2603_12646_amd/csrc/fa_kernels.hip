@@ -208,6 +208,15 @@ __device__ __forceinline__ typename T::v8 load_vt_frag_scalar(const uint16_t* vb
 // multiple of 16.
 __device__ __forceinline__ int k_swz(int r) { return 2 * ((r >> 1) & 3) + ((r >> 3) & 1); }
 __device__ __forceinline__ int v_swz(int r) { return 4 * ((r >> 1) & 1) + 2 * ((r >> 2) & 1); }
+// head_dim 128: a 256-byte row covers all 64 banks by itself and has 16 chunk positions.
+//   K: rows 0..15 at one chunk need 16 different positions, rows 0..7 at a chunk pair too.
+//   V: 4 rows x 4 chunks, or 8 rows x 2 chunks, per 32 lanes.
+__device__ __forceinline__ int k_swz128(int r) { return 2 * (r & 7) + ((r >> 3) & 1); }
+__device__ __forceinline__ int v_swz128(int r) { return 4 * (r & 3) + 2 * ((r >> 2) & 1); }
+template <int D>
+__device__ __forceinline__ int k_swz_d(int r) { return D == 128 ? k_swz128(r) : k_swz(r); }
+template <int D>
+__device__ __forceinline__ int v_swz_d(int r) { return D == 128 ? v_swz128(r) : v_swz(r); }
 
 template <class T>
 __device__ __forceinline__ typename T::v8 load_k_frag_swz(const uint16_t* kblk, int l32, int hh, int ks) {
@@ -921,14 +930,19 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 // ======================================================================================
 // Global kernel: software pipeline over the full tiles + masked ragged tail
 // ======================================================================================
-template <class T, int NQB, int WAVES_PER_EU>
+template <class T, int D, int NQB, int WAVES_PER_EU>
 __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
+  static_assert(D == 64 || D == 128, "pipelined kernel: head_dim 64 or 128");
   constexpr int BM = kWaves * 32 * NQB;
-  // Two stages of 64 x 128-byte rows during the pipeline; the ragged tail reuses the same
-  // storage with padded rows (K 64 x 144 B, V 96 x 160 B), which is why these arrays are
-  // sized by the padded strides.
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * kSK];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * kSV];
+  constexpr int KS = D / 16;  // k-steps of a score block
+  constexpr int DB = D / 32;  // 32-row blocks of O^T
+  constexpr int SK = stride_k(D), SV = stride_v(D);
+  // Two stages of 64 unpadded rows during the pipeline; the ragged tail reuses the same
+  // storage with padded rows (K 64 rows, V 96 rows), which is why these arrays are sized by
+  // the padded strides.
+  static_assert(2 * kBN * SV >= 96 * SV && 2 * kBN * SK >= kWaves * epi_patch(D), "tail and epilogue reuse the stages");
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * SK];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * SV];
 
   TileCoord tc;
   if (!locate_tile<BM>(a, tc)) return;
@@ -945,7 +959,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
 
   if (q0 >= n) {
-    zero_fill<BM>(a, tc, op, lsep);
+    zero_fill<BM, D>(a, tc, op, lsep);
     return;
   }
 
@@ -953,9 +967,9 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const int qw_last = (qw0 + 32 * NQB < n ? qw0 + 32 * NQB : n) - 1;
   const bool wave_has_rows = qw_last >= qw0;
 
-  typename T::v8 qreg[NQB][4];
+  typename T::v8 qreg[NQB][KS];
   load_q<T, NQB>(a, qp, qw0, lane, qreg);
-  RowState<NQB> st;
+  RowState<NQB, D> st;
   init_state(st);
 
   const int nf = n / kBN;  // full tiles: every key visible to every valid query
@@ -973,27 +987,43 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // "tile" of iteration t is K rows [64t+32, 64t+96) and V rows [64t+kVShift, +64).
   constexpr int kVShift = NQB == 1 ? -32 : 0;
   // Pipeline tiles go from HBM/L2 straight into LDS (global_load_lds, 16 bytes per lane):
-  // a wavefront's load fills 1 KB of LDS in lane order, i.e. 8 rows of 128 bytes, so the
-  // LDS tile is unpadded [64 rows][8 chunks of 16 bytes] and bank conflicts are avoided by
-  // choosing WHICH global chunk each lane fetches: chunk position c' of row r holds global
-  // chunk c' ^ k_swz(r) for K and c' ^ v_swz(r) for V.  Wavefront w moves rows 8w..8w+7 of each
-  // 32-row half.  Row bases are wavefront-uniform; each lane adds a fixed offset.  Halves
-  // whose rows would leave [0, N) are only ever the unused ends of the pipeline (V before
-  // block 0, K after the last full block): their base is clamped, their contents unused.
-  const int dl_r = 8 * wave + (lane >> 3);  // row within a 32-row half
-  const uint32_t koff = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane & 7) ^ k_swz(dl_r)) * 8));  // bytes
-  const uint32_t voff = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane & 7) ^ v_swz(dl_r)) * 8));
+  // a wavefront's load fills 1 KB of LDS in lane order, i.e. RPI = 8 rows of 128 bytes
+  // (head_dim 64) or 4 rows of 256 bytes (head_dim 128), so the LDS tile is unpadded
+  // [64 rows][D/8 chunks of 16 bytes] and bank conflicts are avoided by choosing WHICH
+  // global chunk each lane fetches: chunk position c' of row r holds global chunk
+  // c' ^ k_swz(r) for K and c' ^ v_swz(r) for V.  Wavefront w moves rows 8w..8w+7 of each
+  // 32-row half in NI = 8 / RPI loads.  Row bases are wavefront-uniform; each lane adds a
+  // fixed offset.  Halves whose rows would leave [0, N) are only ever the unused ends of
+  // the pipeline (V before block 0, K after the last full block): their base is clamped,
+  // their contents unused.
+  constexpr int CH = D / 8, RPI = 64 / CH, NI = 8 / RPI;
+  uint32_t koff[NI], voff[NI];  // bytes
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int dl_r = 8 * wave + i * RPI + lane / CH;  // row within a 32-row half
+    koff[i] = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane % CH) ^ k_swz_d<D>(dl_r)) * 8));
+    voff[i] = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane % CH) ^ v_swz_d<D>(dl_r)) * 8));
+  }
+  // the four 32-row halves of a tile: global row bases kg / vg, LDS halves kdst / vdst
+  auto fetch_halves = [&](const uint16_t* kga, const uint16_t* kgb, const uint16_t* vga, const uint16_t* vgb,
+                          uint16_t* kstage, uint16_t* vstage) {
+    uint16_t* kdst = kstage + 8 * wave * D;
+    uint16_t* vdst = vstage + 8 * wave * D;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      load16_to_lds(kga, koff[i], kdst + i * RPI * D);
+      load16_to_lds(kgb, koff[i], kdst + 32 * D + i * RPI * D);
+      load16_to_lds(vga, voff[i], vdst + i * RPI * D);
+      load16_to_lds(vgb, voff[i], vdst + 32 * D + i * RPI * D);
+    }
+  };
   auto fetch = [&](int t, uint16_t* kstage, uint16_t* vstage) {
     const int k0r = t * kBN + 32 < 0 ? 0 : t * kBN + 32;
     const int k1r = t * kBN + 64 > N - 32 ? N - 32 : t * kBN + 64;
     const int v0r = t * kBN + kVShift < 0 ? 0 : t * kBN + kVShift;
     const int v1r = t * kBN + kVShift + 32 < 0 ? 0 : t * kBN + kVShift + 32;
-    uint16_t* kdst = kstage + 8 * wave * kD;
-    uint16_t* vdst = vstage + 8 * wave * kD;
-    load16_to_lds(kp + (int64_t)k0r * a.ks[2], koff, kdst);
-    load16_to_lds(kp + (int64_t)k1r * a.ks[2], koff, kdst + 32 * kD);
-    load16_to_lds(vp + (int64_t)v0r * a.vs[2], voff, vdst);
-    load16_to_lds(vp + (int64_t)v1r * a.vs[2], voff, vdst + 32 * kD);
+    fetch_halves(kp + (int64_t)k0r * a.ks[2], kp + (int64_t)k1r * a.ks[2], vp + (int64_t)v0r * a.vs[2],
+                 vp + (int64_t)v1r * a.vs[2], kstage, vstage);
   };
   // Inside the pipeline loop the four row bases just advance by one tile per iteration
   // (scalar 64-bit adds); only the very last tile's second K half can need the clamp.
@@ -1004,34 +1034,29 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const int k1_last_row = n / kBN * kBN > N - 32 ? N - 32 : n / kBN * kBN;  // tile nf-1: min(64 nf, N-32)
   const uint16_t* kg1_last = kp + (int64_t)k1_last_row * a.ks[2];
   auto fetch_next = [&](bool last, uint16_t* kstage, uint16_t* vstage) {
-    uint16_t* kdst = kstage + 8 * wave * kD;
-    uint16_t* vdst = vstage + 8 * wave * kD;
-    load16_to_lds(kg0, koff, kdst);
-    load16_to_lds(last ? kg1_last : kg1, koff, kdst + 32 * kD);
-    load16_to_lds(vg0, voff, vdst);
-    load16_to_lds(vg1, voff, vdst + 32 * kD);
+    fetch_halves(kg0, last ? kg1_last : kg1, vg0, vg1, kstage, vstage);
     kg0 += kBN * a.ks[2];
     kg1 += kBN * a.ks[2];
     vg0 += kBN * a.vs[2];
     vg1 += kBN * a.vs[2];
   };
   // per-lane fragment offsets (16-bit elements) into a 32-row block of a swizzled tile
-  uint32_t kfo[4], vfo[2];
+  uint32_t kfo[KS], vfo[DB];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) kfo[ks] = l32 * kD + (((2 * ks + hh) ^ k_swz(l32)) * 8);
+  for (int ks = 0; ks < KS; ++ks) kfo[ks] = l32 * D + (((2 * ks + hh) ^ k_swz_d<D>(l32)) * 8);
   {
     const int p16 = lane & 15, g = (lane >> 4) & 1;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
-      vfo[db] = (4 * hh + (p16 >> 2)) * kD +
-                (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ v_swz(4 * hh + (p16 >> 2))) * 8) +
+    for (int db = 0; db < DB; ++db)
+      vfo[db] = (4 * hh + (p16 >> 2)) * D +
+                (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ v_swz_d<D>(4 * hh + (p16 >> 2))) * 8) +
                 (p16 & 1) * 4;
   }
   auto k_frag = [&](const uint16_t* kblk, int ks) { return as_v8<T>(*(const uint4*)&kblk[kfo[ks]]); };
   auto vt_frag = [&](const uint16_t* vblk, int ks2, int db) {
     typedef __attribute__((address_space(3))) shortx4 lds_s4;
-    const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + ks2 * 16 * kD]);
-    const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + (ks2 * 16 + 8) * kD]);
+    const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + ks2 * 16 * D]);
+    const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[vfo[db] + (ks2 * 16 + 8) * D]);
     shortx8 x;
     x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
     x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
@@ -1041,22 +1066,22 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // pipeline registers: scores of the current / next unit, packed probabilities of the
   // previous / current unit, operand fragments of the key block in flight
   floatx16 sA, sB;
-  typename T::v8 pA[2], pB[2], ka[4], va[2][2];
+  typename T::v8 pA[2], pB[2], ka[KS], va[2][DB];
   pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
 #pragma unroll
-  for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+  for (int i = 0; i < 2 * DB; ++i) va[i / DB][i % DB] = as_v8<T>(make_uint4(0, 0, 0, 0));
 
   if (nf > 0) {
     // prologue: unit (0,0)'s scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
-    fetch(-1, &lds_k[kBN * kD], &lds_v[kBN * kD]);
+    fetch(-1, &lds_k[kBN * D], &lds_v[kBN * D]);
     fetch(0, lds_k, lds_v);
     wait_direct_loads();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) sA[r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      ka[ks] = k_frag(&lds_k[kBN * kD + 32 * kD], ks);
+    for (int ks = 0; ks < KS; ++ks) {
+      ka[ks] = k_frag(&lds_k[kBN * D + 32 * D], ks);
       sA = T::mfma(ka[ks], qreg[0][ks], sA);
     }
     __syncthreads();  // stage 1 is refilled during iteration 0
@@ -1079,18 +1104,18 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       constexpr bool LOAD = decltype(LOADc)::value;
       if (LOAD) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) ka[ks] = k_frag(kblk, ks);
+        for (int ks = 0; ks < KS; ++ks) ka[ks] = k_frag(kblk, ks);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i >> 1][i & 1] = vt_frag(vblk, i >> 1, i & 1);
+        for (int i = 0; i < 2 * DB; ++i) va[i / DB][i % DB] = vt_frag(vblk, i / DB, i % DB);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
-      // dependent products (the four k-steps of a score block, the two of an output
-      // block) alternate with independent ones
+      // dependent products (the k-steps of a score block, the two of an output block)
+      // alternate with independent ones
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
+      for (int ks = 0; ks < KS; ++ks) {
         s_nxt = T::mfma(ka[ks], qreg[NQ][ks], s_nxt);
-        st.oacc[PQ][ks & 1] = T::mfma(va[ks >> 1][ks & 1], p_prev[ks >> 1], st.oacc[PQ][ks & 1]);
+        st.oacc[PQ][ks % DB] = T::mfma(va[ks / DB][ks % DB], p_prev[ks / DB], st.oacc[PQ][ks % DB]);
       }
       uint32_t pk[8];
       float blk;
@@ -1119,20 +1144,20 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     // per-lane register plus an immediate); the other stage is being filled meanwhile.
     auto iter = [&](auto STAGEc, int t) {
       constexpr int STAGE = decltype(STAGEc)::value;
-      const uint16_t* kt = &lds_k[STAGE * kBN * kD];
-      const uint16_t* vt = &lds_v[STAGE * kBN * kD];
+      const uint16_t* kt = &lds_k[STAGE * kBN * D];
+      const uint16_t* vt = &lds_v[STAGE * kBN * D];
       // the stage being filled was last read in iteration t-1; every wavefront is past
       // that iteration's barrier
-      if (t + 1 < nf) fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * kD], &lds_v[(STAGE ^ 1) * kBN * kD]);
+      if (t + 1 < nf) fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * D], &lds_v[(STAGE ^ 1) * kBN * D]);
       if (wave_has_rows) {
         if constexpr (NQB == 1) {
           unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kD, vt + 32 * kD);
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D);
         } else {
           unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
           unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt, vt);
           unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * kD, vt + 32 * kD);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D);
         }
       }
       wait_direct_loads();  // this wavefront's share of the next tile has landed
@@ -1152,20 +1177,20 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const int tail = n - nf * kBN;
   {
     const int base = nf * kBN;
-    for (int i = tid; i < 96 * 8; i += kThreads) {
-      const int row = i >> 3, c8 = (i & 7) * 8;
+    for (int i = tid; i < 96 * CH; i += kThreads) {
+      const int row = i / CH, c8 = (i % CH) * 8;
       const int jg = base - 32 + row;
       const int jc = jg < 0 ? 0 : (jg < N ? jg : N - 1);
       uint4 vv = *(const uint4*)(vp + jc * a.vs[2] + c8);
       if (jg >= n) vv = make_uint4(0, 0, 0, 0);  // 0 * (anything stored in the padding) must be 0
-      *(uint4*)&lds_v[row * kSV + c8] = vv;
+      *(uint4*)&lds_v[row * SV + c8] = vv;
     }
     if (tail > 0) {
-      for (int i = tid; i < 64 * 8; i += kThreads) {
-        const int row = i >> 3, c8 = (i & 7) * 8;
+      for (int i = tid; i < 64 * CH; i += kThreads) {
+        const int row = i / CH, c8 = (i % CH) * 8;
         const int jg = base + row;
         const int jc = jg < N ? jg : N - 1;
-        *(uint4*)&lds_k[row * kSK + c8] = *(const uint4*)(kp + jc * a.ks[2] + c8);
+        *(uint4*)&lds_k[row * SK + c8] = *(const uint4*)(kp + jc * a.ks[2] + c8);
       }
     }
   }
@@ -1177,8 +1202,8 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const typename T::v8 vf = load_vt_frag<T>(lds_v, lane, ks2, db);
+        for (int db = 0; db < DB; ++db) {
+          const typename T::v8 vf = load_vt_frag<T, D>(lds_v, lane, ks2, db);
           st.oacc[NQB - 1][db] = T::mfma(vf, pA[ks2], st.oacc[NQB - 1][db]);
         }
     }
@@ -1193,13 +1218,13 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       for (int kb = 0; kb < 2; ++kb) {
         const int kb0 = nf * kBN + kb * 32;
         if (kb0 >= n) continue;
-        simple_block<T, NQB, true, 0>(st, qreg, &lds_k[kb * 32 * kSK], &lds_v[(32 + kb * 32) * kSV], kb0,
-                                         jlo, jhi, lane, c, tau_raw);
+        simple_block<T, NQB, true, 0>(st, qreg, &lds_k[kb * 32 * SK], &lds_v[(32 + kb * 32) * SV], kb0,
+                                      jlo, jhi, lane, c, tau_raw);
       }
     }
   }
   __syncthreads();  // tail consumed: the K storage becomes the epilogue patches
-  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
+  epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, lds_k + wave * epi_patch(D));
 }
 
 template <class T>
@@ -1211,8 +1236,11 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
-  if (a.head_dim != kD) {
-    // head_dim 32 / 128: the masked kernel covers every mask; bm is 128 here
+  if (a.head_dim == 128 && global && v_path == 0) {
+    hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2>), dim3(grid), block, 0, s, a);
+  } else if (a.head_dim != kD) {
+    // head_dim 32, and the local layers of head_dim 128: the masked kernel covers every
+    // mask; bm is 128 here
     if (a.head_dim == 32) {
       if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true>), dim3(grid), block, 0, s, a);
       else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, false>), dim3(grid), block, 0, s, a);
@@ -1221,8 +1249,8 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
       else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, false>), dim3(grid), block, 0, s, a);
     }
   } else if (global && v_path == 0) {
-    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 2, 2>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 1, 2>), dim3(grid), block, 0, s, a);
+    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
     // 32-key blocks a 128-row query tile can touch (tiles start at multiples of 128)
     const bool two_sided = a.wl >= 0 && a.wr >= 0;

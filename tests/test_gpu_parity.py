@@ -12,7 +12,7 @@ import torch
 
 import paper_2603_12646_amd as fa
 from oracle.attention_oracle import attention_oracle, attention_oracle_rows, window_from_width
-from workloads import CONFIGS, draw, make_inputs, round_to_storage
+from workloads import ALL_CONFIGS, CONFIGS, draw, make_inputs, round_to_storage
 
 from tests.gpu_util import (FA_DT, LSE_TOL, TOL, check_against, poison, run_ex, run_simple, to_dev)
 
@@ -292,12 +292,12 @@ def sample_rows(n, rng, count):
     return np.array(sorted(edge | set(rest)), dtype=np.int64)
 
 
-@pytest.mark.parametrize("name", ["c3_8k", "c4_16k_x3", "c5a_32k_global", "c5b_32k_local"])
+@pytest.mark.parametrize("name", ["c3_8k", "c4_16k_x3", "c5a_32k_global", "c5b_32k_local", "d128_8k", "d128_32k"])
 def test_named_large_configs_sampled_rows(name):
     """Full-size launch, as bench.py times it; the oracle recomputes sampled query
     rows (the first and last 130 valid rows of every (batch, head) plus random ones)
     one by one against the full key range.  Padded rows are checked exhaustively."""
-    w = CONFIGS[name]
+    w = ALL_CONFIGS[name]
     lens, q, k, v = make_inputs(w)
     L, R = window_from_width(w.window)
     o, lse = run_simple(q, k, v, lens, w.dtype, w.scale, w.window)

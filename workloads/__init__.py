@@ -19,7 +19,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-__all__ = ["Workload", "CONFIGS", "round_to_storage", "draw", "make_inputs"]
+__all__ = ["Workload", "CONFIGS", "NEXT_CONFIGS", "ALL_CONFIGS", "round_to_storage", "draw", "make_inputs"]
 
 
 def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
@@ -90,6 +90,15 @@ def draw(seed, batch, heads, max_len, head_dim, dtype, qk_gain=1.0, random_lens=
         q *= np.float32(qk_gain)
         k *= np.float32(qk_gain)
     return lens, round_to_storage(q, dtype), round_to_storage(k, dtype), round_to_storage(v, dtype)
+
+# Workloads for the operator's other head sizes (paper Sec. 4.1.3: run-time dispatch on
+# head_dim 32 / 64 / 128).  Not among the five above: 8 heads of 128 (hidden size 1024),
+# scale 1/sqrt(128), otherwise the recipe of the 8K and 32K global workloads.
+NEXT_CONFIGS = {
+    "d128_8k": Workload("d128_8k", 5, "fp16", 1, 8, 8192, 128, 128 ** -0.5, -1, (7900,), qk_gain=1.5),
+    "d128_32k": Workload("d128_32k", 6, "bf16", 1, 8, 32768, 128, 128 ** -0.5, -1, None),
+}
+ALL_CONFIGS = {**CONFIGS, **NEXT_CONFIGS}
 
 
 def make_inputs(w: Workload):
