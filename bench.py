@@ -105,6 +105,21 @@ def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0):
     return wall_ms / steps, ev_ms / steps
 
 
+def measured_ceilings():
+    """What this machine sustains with nothing but matrix-core instructions (zero and random
+    operands) and with a plain copy: the program built from csrc/ceilings.hip, run as a child
+    process.  Context for roofline.frac, which is quoted against the published peaks."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2603_12646_amd", "fa_ceilings")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        return json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
+    except Exception:
+        return None
+
+
 def cpu_baseline(w, lens, q, k, v, budget_s=15.0):
     """The fp64 oracle as it stands, timed on this host on whole (batch, head) slices
     until about budget_s seconds have been spent."""
@@ -153,6 +168,8 @@ def main():
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-others", action="store_true", help="time only the named workload")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured matrix-core / copy ceilings (a child process of about a second)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 256 MiB three times, so a rocprofv3 "
                          "--pmc run of this command has a kernel of known traffic to scale against")
@@ -202,6 +219,15 @@ def main():
                    "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning},
         "roofline": roof,
     }
+
+    if not args.no_ceilings:
+        ceil = measured_ceilings()
+        out["ceilings"] = ceil
+        if ceil and not hbm_bound:
+            key = "mfma_f16_random_tflops" if w.dtype == "fp16" else "mfma_bf16_random_tflops"
+            roof["frac_of_measured_random_data_ceiling"] = roof["achieved"] / ceil[key]
+        elif ceil:
+            roof["frac_of_measured_copy"] = roof["achieved"] / ceil["copy_gbs"]
 
     if args.calibrate_copy:
         src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")   # 256 MiB
