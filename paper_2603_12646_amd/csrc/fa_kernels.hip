@@ -1,5 +1,5 @@
-// Flash-attention forward for gfx950 (MI355X): head_dim 64, fp16 / bf16 storage,
-// fp32 accumulation, key-padding mask by sequence length, optional local window.
+// Flash-attention forward for gfx950 (MI355X): head_dim 64 (also 32 and 128), fp16 / bf16
+// storage, fp32 accumulation, key-padding mask by sequence length, optional local window.
 //
 // The operation is softmax(scale * Q K^T + mask) V per (batch, head), evaluated
 // one key block at a time with a running row maximum and row sum so that no
@@ -9,7 +9,7 @@
 // Work decomposition (one workgroup = 4 wavefronts = 256 threads):
 //   * a workgroup owns BM = 4*32*NQB query rows of one (batch, head); each
 //     wavefront owns NQB blocks of 32 query rows and keeps their Q fragments,
-//     running maximum / sum and the 64-wide output accumulator in registers;
+//     running maximum / sum and the head_dim-wide output accumulator in registers;
 //   * K and V are streamed through LDS, fetched from HBM/L2 ahead of the arithmetic
 //     (in the main kernels with direct global->LDS loads into an unpadded, XOR-swizzled
 //     tile; in the reference masked kernel through registers into a padded tile).
@@ -35,7 +35,7 @@
 // result is unchanged because numerator and denominator share the reference.
 //
 // Kernels:
-//   fa_fwd_global_kernel  global layers (no window).  Full 64-key tiles run in a
+//   fa_fwd_global_kernel  global layers (no window), head_dim 64 or 128.  Full 64-key tiles run in a
 //       software pipeline over 32-key x 32-query units: while the vector ALU turns unit
 //       w's scores into probabilities, the matrix cores compute unit w+1's scores and
 //       accumulate unit w-1's P.V.  The ragged last tile takes the masked block.
@@ -43,8 +43,9 @@
 //       LDS (the paper's 63/64 window): everything is requested at once, then each
 //       wavefront runs the same pipeline over the blocks its queries can see.
 //   fa_fwd_window_kernel  wider or one-sided windows: ring of 32-key stages.
-//   fa_fwd_masked_kernel  reference path (register staging, padded tiles, optional
-//       16-bit V reads), kept as an independent implementation for the tests.
+//   fa_fwd_masked_kernel  general path (register staging, padded tiles, optional 16-bit V
+//       reads) for head_dim 32, 64, 128: the production path of head_dim 32 and of the local
+//       layers of head_dim 128, and at head_dim 64 an independent implementation for the tests.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
