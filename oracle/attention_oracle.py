@@ -12,6 +12,9 @@ window_size_right; Eq. 1: the 1-D key-padding bias):
 
     for every batch b, head h and query row i < n_b
         s_j   = scale * sum_d Q[i,d] K[j,d]                for every key j < N
+        s_j  += key_bias[b, j]   when an additive 1-D key bias is given (the operator's
+                                 pad_bias input, Sec. 4.1.3 / Eq. 1: one value per key,
+                                 shared by all heads and queries, NOT multiplied by scale)
         s_j   = -inf  where key j is not visible
         m     = max_j s_j,  e_j = exp(s_j - m),  l = sum_j e_j
         o[i]  = sum_j (e_j / l) V[j],   lse[i] = m + ln(l)
@@ -34,13 +37,17 @@ Readings where the paper is silent (kept in step with the design notes):
   * padding is a tail: keys/queries j >= n_b are padding;
   * padded query rows and rows with no visible key give o = 0, lse = -inf;
   * lse is the natural-log logsumexp of the scaled, masked scores;
-  * window positions are absolute token indices, clipped at 0 and n_b.
+  * window positions are absolute token indices, clipped at 0 and n_b;
+  * a key bias of -inf excludes that key (an arbitrary, non-tail key mask); finite
+    values are added literally, so the paper's -65504 on padded keys is also accepted.
 
 Pins (tests/test_oracle_pins.py, no GPU): pure-Python brute force on tiny
 inputs, scipy softmax/logsumexp and torch-CPU SDPA on special cases, closed
 forms (Q = 0, L = R = 0, one-hot limit), invariants (rows of P sum to 1,
 constant V, key permutation, masked keys have no effect, key shift,
-split/merge identity).  Parity with the paper's trained-model activations is
+split/merge identity); for the key bias: brute force, ln(w_j) bias = key j repeated
+w_j times, constant bias shifts lse only, -inf bias = key removed, -65504 on the tail
+= the literal form of Eq. 1.  Parity with the paper's trained-model activations is
 unpinned: no weights or tensors are published with the paper.
 """
 from __future__ import annotations
@@ -86,10 +93,13 @@ def visible_mask(rows: np.ndarray, n_keys_total: int, n_valid: int, left: int, r
     return vis
 
 
-def _rows_one_head(q, k, v, rows, n_valid, scale, left, right, want_p):
-    """Attention for the given query rows of one (batch, head). q,k,v: [N, D] float64."""
+def _rows_one_head(q, k, v, rows, n_valid, scale, left, right, want_p, key_bias=None):
+    """Attention for the given query rows of one (batch, head). q,k,v: [N, D] float64;
+    key_bias: None or [N] float64, added to the scaled scores."""
     n_total = k.shape[0]
     s = (q[rows] @ k.T) * scale                      # full score rows, [R, N]
+    if key_bias is not None:
+        s = s + key_bias[None, :]
     vis = visible_mask(rows, n_total, n_valid, left, right)
     s = np.where(vis, s, -np.inf)
     m = s.max(axis=1)                                # [R]
@@ -108,8 +118,9 @@ def _rows_one_head(q, k, v, rows, n_valid, scale, left, right, want_p):
 
 
 def attention_oracle(q, k, v, seq_lens=None, scale=1.0, left=-1, right=-1,
-                     row_block=256, return_p=False):
+                     row_block=256, return_p=False, key_bias=None):
     """Full oracle. q, k, v: [B, H, N, D] (any float dtype; converted exactly to fp64).
+    key_bias: None or [B, N], one additive value per key (-inf excludes the key).
 
     seq_lens: None (every sequence has N valid tokens) or B integers; values are
     clamped into [0, N].  Returns (o [B,H,N,D] fp64, lse [B,H,N] fp64) and, when
@@ -121,6 +132,8 @@ def attention_oracle(q, k, v, seq_lens=None, scale=1.0, left=-1, right=-1,
     B, H, N, D = q.shape
     if seq_lens is None:
         seq_lens = [N] * B
+    if key_bias is not None:
+        key_bias = np.asarray(key_bias, dtype=np.float64).reshape(B, N)
     o = np.zeros((B, H, N, D), dtype=np.float64)
     lse = np.full((B, H, N), -np.inf, dtype=np.float64)
     P = np.zeros((B, H, N, N), dtype=np.float64) if return_p else None
@@ -130,7 +143,8 @@ def attention_oracle(q, k, v, seq_lens=None, scale=1.0, left=-1, right=-1,
             for r0 in range(0, n, row_block):
                 rows = np.arange(r0, min(n, r0 + row_block))
                 ob, lb, pb = _rows_one_head(q[b, h], k[b, h], v[b, h], rows, n,
-                                            scale, left, right, return_p)
+                                            scale, left, right, return_p,
+                                            None if key_bias is None else key_bias[b])
                 o[b, h, rows] = ob
                 lse[b, h, rows] = lb
                 if return_p:
@@ -140,8 +154,9 @@ def attention_oracle(q, k, v, seq_lens=None, scale=1.0, left=-1, right=-1,
     return o, lse
 
 
-def attention_oracle_rows(q, k, v, b, h, rows, n_valid, scale=1.0, left=-1, right=-1):
+def attention_oracle_rows(q, k, v, b, h, rows, n_valid, scale=1.0, left=-1, right=-1, key_bias=None):
     """Oracle for selected query rows of one (b, h): used to sample large configs.
+    key_bias: None or [B, N].
 
     q, k, v: [B, H, N, D] in any float dtype; only the (b, h) slice is converted.
     rows must all be < n_valid.  Returns (o [len(rows), D], lse [len(rows)]).
@@ -152,7 +167,8 @@ def attention_oracle_rows(q, k, v, b, h, rows, n_valid, scale=1.0, left=-1, righ
     rows = np.asarray(rows, dtype=np.int64)
     if rows.size and (rows.min() < 0 or rows.max() >= n_valid):
         raise ValueError("sampled rows must be valid query rows")
-    o, lse, _ = _rows_one_head(qh, kh, vh, rows, int(n_valid), scale, left, right, False)
+    kb = None if key_bias is None else np.asarray(key_bias, dtype=np.float64)[b]
+    o, lse, _ = _rows_one_head(qh, kh, vh, rows, int(n_valid), scale, left, right, False, kb)
     return o, lse
 
 

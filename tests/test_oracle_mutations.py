@@ -24,6 +24,10 @@ MUTATIONS = {
     "wrong sign in exp": ("np.exp(s - m_safe[:, None])", "np.exp(m_safe[:, None] - s)"),
     "window width mapping": ("return ((window - 1) // 2, window // 2)", "return (window // 2, window // 2)"),
     "window halves swapped": ("return ((window - 1) // 2, window // 2)", "return (window // 2, (window - 1) // 2)"),
+    "key bias dropped": ("s = s + key_bias[None, :]", "s = s"),
+    "key bias subtracted": ("s = s + key_bias[None, :]", "s = s - key_bias[None, :]"),
+    "key bias multiplied by scale": ("s = s + key_bias[None, :]", "s = s + key_bias[None, :] * scale"),
+    "key bias of another batch element": ("None if key_bias is None else key_bias[b])", "None if key_bias is None else key_bias[0])"),
     "padded rows computed": ("for r0 in range(0, n, row_block):\n                rows = np.arange(r0, min(n, r0 + row_block))",
                              "for r0 in range(0, N, row_block):\n                rows = np.arange(r0, min(N, r0 + row_block))"),
 }
@@ -42,6 +46,10 @@ BATTERY = [
     (pins.test_split_merge_identity, [()]),
     (pins.test_masked_keys_have_no_effect_even_nan, [()]),
     (pins.test_seq_len_clamping_and_empty, [()]),
+    (pins.test_key_bias_brute_force, [(-1, -1, (7, 5)), (1, 2, (8, 3))]),
+    (pins.test_key_bias_log_weight_equals_repeated_keys, [()]),
+    (pins.test_key_bias_constant_shifts_lse_only, [()]),
+    (pins.test_key_bias_minus_inf_removes_the_key, [()]),
 ]
 
 NAMES = ["attention_oracle", "attention_oracle_rows", "additive_bias_variant", "visible_mask", "window_from_width"]

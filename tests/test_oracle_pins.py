@@ -21,7 +21,7 @@ def rand(shape, seed):
 # --------------------------------------------------------------------------
 # brute force: pure-Python floats, written from the definition, no numpy math
 # --------------------------------------------------------------------------
-def brute(q, k, v, lens, scale, left, right):
+def brute(q, k, v, lens, scale, left, right, bias=None):
     B, H, N, D = q.shape
     o = [[[[0.0] * D for _ in range(N)] for _ in range(H)] for _ in range(B)]
     lse = [[[-math.inf] * N for _ in range(H)] for _ in range(B)]
@@ -38,7 +38,10 @@ def brute(q, k, v, lens, scale, left, right):
                     dot = 0.0
                     for d in range(D):
                         dot += float(q[b, h, i, d]) * float(k[b, h, j, d])
-                    terms.append((j, scale * dot))
+                    extra = 0.0 if bias is None else float(bias[b][j])
+                    if extra == -math.inf:
+                        continue
+                    terms.append((j, scale * dot + extra))
                 if not terms:
                     continue
                 big = max(t for _, t in terms)
@@ -318,3 +321,76 @@ def test_seq_len_clamping_and_empty():
     assert np.all(o[:2] == 0) and np.all(np.isneginf(lse[:2]))
     o_full, lse_full = attention_oracle(q[2:], k[2:], v[2:], None, 1.0)
     assert np.array_equal(o[2], o_full[0]) and np.array_equal(lse[2], lse_full[0])
+
+
+# --------------------------------------------------------------------------
+# additive 1-D key bias (the operator's pad_bias input, Sec. 4.1.3 / Eq. 1)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("left,right,lens", [(-1, -1, (7, 5)), (1, 2, (8, 3)), (0, 0, (8, 8)), (2, -1, (1, 6))])
+def test_key_bias_brute_force(left, right, lens):
+    B, H, N, D = 2, 2, 8, 4
+    q, k, v = rand((B, H, N, D), 31), rand((B, H, N, D), 32), rand((B, H, N, D), 33)
+    bias = rand((B, N), 34) * 2.0
+    bias[0, 2] = -math.inf          # a masked key in the middle of the sequence
+    bias[1, 0] = -65504.0
+    o, lse = attention_oracle(q, k, v, lens, 0.41, left, right, row_block=3, key_bias=bias)
+    ob, lb = brute(q, k, v, lens, 0.41, left, right, bias)
+    fin = np.isfinite(lb)
+    assert np.allclose(o, ob, rtol=0, atol=1e-12)
+    assert np.array_equal(fin, np.isfinite(lse)) and np.allclose(lse[fin], lb[fin], rtol=0, atol=1e-12)
+
+
+def test_key_bias_log_weight_equals_repeated_keys():
+    """bias_j = ln(w_j) with integer w_j is attention over a sequence in which key j (and
+    its value) appears w_j times: fixes the sign of the bias and that scale does not touch it."""
+    H, N, D = 2, 6, 4
+    q, k, v = rand((1, H, N, D), 35), rand((1, H, N, D), 36), rand((1, H, N, D), 37)
+    w = np.array([1, 3, 2, 1, 4, 2])
+    o, lse = attention_oracle(q, k, v, None, 0.7, key_bias=np.log(w)[None, :])
+    idx = np.repeat(np.arange(N), w)
+    M = len(idx)
+    q2 = np.zeros((1, H, M, D)); q2[:, :, :N] = q
+    o2, lse2 = attention_oracle(q2, k[:, :, idx], v[:, :, idx], None, 0.7)
+    assert np.allclose(o, o2[:, :, :N], rtol=0, atol=1e-13)
+    assert np.allclose(lse, lse2[:, :, :N], rtol=0, atol=1e-13)
+
+
+def test_key_bias_constant_shifts_lse_only():
+    B, H, N, D = 2, 2, 9, 4
+    q, k, v = rand((B, H, N, D), 38), rand((B, H, N, D), 39), rand((B, H, N, D), 40)
+    lens = (9, 6)
+    o0, l0 = attention_oracle(q, k, v, lens, 0.3, 2, 3)
+    o1, l1 = attention_oracle(q, k, v, lens, 0.3, 2, 3, key_bias=np.full((B, N), 1.25))
+    fin = np.isfinite(l0)
+    assert np.allclose(o0, o1, rtol=0, atol=1e-13)
+    assert np.allclose(l1[fin], l0[fin] + 1.25, rtol=0, atol=1e-13) and np.all(l1[~fin] == -np.inf)
+
+
+def test_key_bias_minus_inf_removes_the_key():
+    """A non-tail key mask: -inf on keys {1, 4} equals attention over the remaining keys."""
+    H, N, D = 2, 7, 4
+    q, k, v = rand((1, H, N, D), 41), rand((1, H, N, D), 42), rand((1, H, N, D), 43)
+    bias = np.zeros((1, N)); bias[0, [1, 4]] = -np.inf
+    o, lse = attention_oracle(q, k, v, None, 0.9, key_bias=bias)
+    keep = [0, 2, 3, 5, 6]
+    for h in range(H):
+        sc = 0.9 * q[0, h] @ k[0, h, keep].T
+        p = scipy.special.softmax(sc, axis=1)
+        assert np.allclose(o[0, h], p @ v[0, h, keep], rtol=0, atol=1e-13)
+        assert np.allclose(lse[0, h], scipy.special.logsumexp(sc, axis=1), rtol=0, atol=1e-13)
+    # every key masked: same convention as a row with no visible key
+    o2, lse2 = attention_oracle(q, k, v, None, 0.9, key_bias=np.full((1, N), -np.inf))
+    assert np.all(o2 == 0) and np.all(lse2 == -np.inf)
+
+
+def test_key_bias_literal_eq1_form():
+    """-65504 on the padded tail with every key 'valid' is the literal Eq. 1 computation."""
+    B, H, N, D = 2, 2, 10, 4
+    q, k, v = rand((B, H, N, D), 44), rand((B, H, N, D), 45), rand((B, H, N, D), 46)
+    lens = (10, 6)
+    bias = np.where(np.arange(N)[None, :] < np.array(lens)[:, None], 0.0, -65504.0)
+    o, lse = attention_oracle(q, k, v, None, 0.5, key_bias=bias)
+    ov, lv = additive_bias_variant(q, k, v, lens, 0.5)
+    for b, n in enumerate(lens):
+        assert np.allclose(o[b, :, :n], ov[b, :, :n], rtol=0, atol=1e-13)
+        assert np.allclose(lse[b, :, :n], lv[b, :, :n], rtol=0, atol=1e-13)
