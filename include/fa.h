@@ -58,7 +58,7 @@
 extern "C" {
 #endif
 
-#define FA_VERSION 100 /* major*10000 + minor*100 + patch */
+#define FA_VERSION 200 /* major*10000 + minor*100 + patch */
 
 enum {
   FA_OK = 0,
@@ -103,7 +103,8 @@ int fa_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse
  * fa_fwd_ex: superset entry point.  Separate left / right window extents (the
  * paper's window_size_left / window_size_right attributes: < 0 = unbounded on
  * that side), explicit element strides (so [batch, len, heads, dim] or a packed
- * QKV buffer can be passed without a transpose), and a tuning word.
+ * QKV buffer can be passed without a transpose), an additive 1-D key bias, and a
+ * tuning word.
  *
  * Strides are in ELEMENTS; the head_dim axis always has stride 1.  A stride
  * triple that is all zero selects the dense [batch, heads, max_len, head_dim]
@@ -131,6 +132,15 @@ typedef struct fa_params {
   uint32_t tuning; /* 0 = library's choice; FA_TUNE_* bits force a kernel shape
                       (for benchmarking sweeps; results are identical up to
                       summation order) */
+  /* Additive key bias, the operator's pad_bias input (paper Sec. 4.1.3, Eq. 1): DEVICE
+     pointer to [batch, max_len] values of the SAME 16-bit type as q/k/v, or NULL.
+     key_bias[b, j] is added to scale * q_i.k_j for every head and query (it is not
+     multiplied by scale); -infinity excludes key j, so any key mask can be expressed,
+     and the paper's -65504 on padded keys works as written.  It applies on top of
+     seq_lens and the window.  2-byte alignment.  A call with a key bias runs the
+     general (masked) kernel. */
+  const void* key_bias;
+  int64_t key_bias_stride; /* elements between batch rows; 0 = max_len; >= max_len */
 } fa_params;
 
 /* tuning word: bits 0-3 query rows per workgroup, bits 4-7 V-operand path,

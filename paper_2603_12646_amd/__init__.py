@@ -57,6 +57,8 @@ class FaParams(ctypes.Structure):
         ("o_strides", ctypes.c_int64 * 3),
         ("stream", ctypes.c_void_p),
         ("tuning", ctypes.c_uint32),
+        ("key_bias", ctypes.c_void_p),
+        ("key_bias_stride", ctypes.c_int64),
     ]
 
 
@@ -151,7 +153,8 @@ def fa_fwd_bf16(q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scal
 
 def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_len, head_dim=64,
               scale, window_left=-1, window_right=-1, q_strides=None, k_strides=None,
-              v_strides=None, o_strides=None, stream=None, tuning=0, check=True):
+              v_strides=None, o_strides=None, stream=None, tuning=0, key_bias=None,
+              key_bias_stride=0, check=True):
     """Fill an fa_params struct and call fa_fwd_ex."""
     p = FaParams()
     p.struct_size = ctypes.sizeof(FaParams)
@@ -168,4 +171,5 @@ def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_l
             arr[i] = 0 if val is None else int(val[i])
     p.stream = _stream(stream)
     p.tuning = tuning
+    p.key_bias, p.key_bias_stride = _ptr(key_bias), key_bias_stride
     return _check(load_library().fa_fwd_ex(ctypes.byref(p)), check)

@@ -62,9 +62,9 @@ __global__ __launch_bounds__(256) void copy16(const uint4* __restrict__ src, uin
   for (size_t base = (size_t)blockIdx.x * piece; base + piece <= n; base += (size_t)gridDim.x * piece) {
     uint4 r[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = __builtin_nontemporal_load(&src[base + j * 256 + threadIdx.x]);
+    for (int j = 0; j < 4; ++j) r[j] = src[base + j * 256 + threadIdx.x];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(r[j], &dst[base + j * 256 + threadIdx.x]);
+    for (int j = 0; j < 4; ++j) dst[base + j * 256 + threadIdx.x] = r[j];
   }
 }
 

@@ -64,6 +64,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->o))
     return FA_ERR_MISALIGNED;
   if (p->lse && (reinterpret_cast<uintptr_t>(p->lse) & 3u)) return FA_ERR_MISALIGNED;
+  if (p->key_bias && (reinterpret_cast<uintptr_t>(p->key_bias) & 1u)) return FA_ERR_MISALIGNED;
+  if (p->key_bias_stride < 0 || (p->key_bias && p->key_bias_stride != 0 && p->key_bias_stride < p->max_len))
+    return FA_ERR_BAD_SHAPE;
   if (p->tuning & ~0x333u) return FA_ERR_BAD_TUNING;
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
   if (t_bm > FA_TUNE_BM_256 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
@@ -78,7 +81,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
 
   // head_dim 32 and 128 run the 128-row kernel only (the tile-size hint is ignored there)
-  const int bm = p->head_dim != 64 ? 128
+  const int bm = (p->head_dim != 64 || p->key_bias) ? 128
                                    : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
   const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
   const int64_t total = n_qtiles * p->batch * p->heads;
@@ -88,6 +91,8 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
 
   a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o; a.lse = p->lse; a.seq_lens = p->seq_lens;
   a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len; a.head_dim = p->head_dim;
+  a.key_bias = p->key_bias;
+  a.kb_stride = p->key_bias_stride ? p->key_bias_stride : p->max_len;
   const float c = std::fabs(p->scale) * kLog2e;
   a.c = c;
   a.negate_q = std::signbit(p->scale) && p->scale != 0.0f ? 1 : 0;

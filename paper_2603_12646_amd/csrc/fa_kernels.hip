@@ -96,6 +96,7 @@ struct F16 {
   static __device__ __forceinline__ float sum2(uint32_t pk, float acc) {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, pk), (half2v){1, 1}, acc, false);
   }
+  static __device__ __forceinline__ float to_float(uint16_t x) { return (float)__builtin_bit_cast(_Float16, x); }
 };
 
 struct BF16 {
@@ -112,6 +113,7 @@ struct BF16 {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2v, pk),
                                            (bf2v){(__bf16)1.0f, (__bf16)1.0f}, acc, false);
   }
+  static __device__ __forceinline__ float to_float(uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); }
 };
 
 // Exchange between the two lanes (l, l ^ 32) that hold the same query: afterwards
@@ -315,11 +317,14 @@ __device__ __forceinline__ uint32_t visible_bits(int kb0, int hh, int jlo, int j
 // is the visible key range of the lane's query.  FRAG selects how operands come out of
 // LDS: 0 padded tile + transpose read, 1 padded tile + 16-bit reads, 2 swizzled tile +
 // transpose read.
+//
+// bias2 (optional): 32 floats in LDS, the block's additive key bias times log2(e).  With a
+// bias the row state is kept in the log2 domain (m_ref = mc = reference of s*c + bias2).
 template <class T, int NQB, bool MASKED, int FRAG, int D>
 __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typename T::v8 (&qreg)[NQB][D / 16],
                                              const uint16_t* kblk, const uint16_t* vblk, int kb0,
                                              const int (&jlo)[NQB], const int (&jhi)[NQB], int lane,
-                                             float c, float tau_raw) {
+                                             float c, float tau_raw, const float* bias2 = nullptr) {
   const int l32 = lane & 31, hh = lane >> 5;
   floatx16 sacc[NQB];
 #pragma unroll
@@ -345,24 +350,56 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
         vis |= (jg >= jlo[qb] && jg <= jhi[qb]) ? (1u << r) : 0u;
       }
     }
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float sv = (!MASKED || (vis >> r & 1)) ? sacc[qb][r] : -INFINITY;
-      tmax = fmaxf(tmax, sv);
-    }
-    tmax = max_xor32(tmax);
-    const bool refresh = (tmax - st.m_ref[qb]) > tau_raw;
-    if (__any(refresh)) rescale_rows(st, qb, refresh, tmax, c);
-    const float nmc = -st.mc[qb];
     float p[16];
-    float ls = st.lsum[qb];
+    float ls;  // read after a possible rescale of the row state
+    if (bias2) {
+      // scores in the log2 domain, bias included; the reference lives in the same domain
+      float t[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], c, nmc));
-      if (MASKED) e = (vis >> r & 1) ? e : 0.f;
-      p[r] = e;
-      ls += e;
+      for (int g = 0; g < 4; ++g) {
+        const float4 b4 = *(const float4*)&bias2[8 * g + 4 * hh];
+        t[4 * g + 0] = __builtin_fmaf(sacc[qb][4 * g + 0], c, b4.x);
+        t[4 * g + 1] = __builtin_fmaf(sacc[qb][4 * g + 1], c, b4.y);
+        t[4 * g + 2] = __builtin_fmaf(sacc[qb][4 * g + 2], c, b4.z);
+        t[4 * g + 3] = __builtin_fmaf(sacc[qb][4 * g + 3], c, b4.w);
+      }
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (MASKED && !(vis >> r & 1)) t[r] = -INFINITY;
+        tmax = fmaxf(tmax, t[r]);
+      }
+      tmax = max_xor32(tmax);
+      const bool refresh = (tmax - st.m_ref[qb]) > 8.0f;
+      if (__any(refresh)) rescale_rows(st, qb, refresh, tmax, 1.0f);
+      const float mcq = st.mc[qb];
+      ls = st.lsum[qb];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float e = __builtin_amdgcn_exp2f(t[r] - mcq);
+        if (MASKED) e = (vis >> r & 1) ? e : 0.f;
+        p[r] = e;
+        ls += e;
+      }
+    } else {
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float sv = (!MASKED || (vis >> r & 1)) ? sacc[qb][r] : -INFINITY;
+        tmax = fmaxf(tmax, sv);
+      }
+      tmax = max_xor32(tmax);
+      const bool refresh = (tmax - st.m_ref[qb]) > tau_raw;
+      if (__any(refresh)) rescale_rows(st, qb, refresh, tmax, c);
+      const float nmc = -st.mc[qb];
+      ls = st.lsum[qb];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], c, nmc));
+        if (MASKED) e = (vis >> r & 1) ? e : 0.f;
+        p[r] = e;
+        ls += e;
+      }
     }
     st.lsum[qb] = ls;
 #pragma unroll
@@ -518,13 +555,14 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB, D>
 // ======================================================================================
 // Masked kernel: windows (and any tile that needs per-element masks)
 // ======================================================================================
-template <class T, int D, int NQB, bool V_TR>
+template <class T, int D, int NQB, bool V_TR, bool BIAS = false>
 __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32 * NQB;
   constexpr int SK = stride_k(D), SV = stride_v(D);
   static_assert(2 * kBN * SK >= kWaves * epi_patch(D), "the K stages double as the epilogue patches");
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kBN * SK];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kBN * SV];
+  __shared__ __attribute__((aligned(16))) float lds_b[2][BIAS ? kBN : 4];  // key bias * log2(e) of the tile
 
   TileCoord tc;
   if (!locate_tile<BM>(a, tc)) return;
@@ -585,6 +623,8 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
     // padded V rows are replaced by zeros: 0 * (whatever is stored there) must be 0
     if (jg >= n) vv = make_uint4(0, 0, 0, 0);
   };
+  const uint16_t* bp = BIAS ? (const uint16_t*)a.key_bias + tc.b * a.kb_stride : nullptr;
+  float bst = 0.f;  // threads 0..63: the bias of key t*64 + tid
   auto fetch = [&](int t) {
     fetch_row(t * kBN + st_r, kst0, vst0);
     if (NST > 1) fetch_row(t * kBN + RS + st_r, kst1, vst1);
@@ -592,8 +632,13 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
       fetch_row(t * kBN + 2 * RS + st_r, kst2, vst2);
       fetch_row(t * kBN + 3 * RS + st_r, kst3, vst3);
     }
+    if (BIAS && tid < kBN) {
+      const int jg = t * kBN + tid;
+      bst = T::to_float(bp[jg < N ? jg : N - 1]) * 1.44269504088896340736f;
+    }
   };
   auto stash = [&](int buf) {
+    if (BIAS && tid < kBN) lds_b[buf][tid] = bst;
     *(uint4*)&lds_k[buf][st_r * SK + st_c] = kst0;
     *(uint4*)&lds_v[buf][st_r * SV + st_c] = vst0;
     if (NST > 1) {
@@ -624,7 +669,8 @@ __global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelA
         if (a.wl >= 0 && kb0 + 31 < qw0 - a.wl) continue;
         if (a.wr >= 0 && kb0 > qw_last + a.wr) continue;
         simple_block<T, NQB, true, V_TR ? 0 : 1>(st, qreg, &lds_k[buf][kb * 32 * SK], &lds_v[buf][kb * 32 * SV],
-                                                 kb0, jlo, jhi, lane, a.c, a.tau_raw);
+                                                 kb0, jlo, jhi, lane, a.c, a.tau_raw,
+                                                 BIAS ? &lds_b[buf][kb * 32] : nullptr);
       }
     }
     if (t + 1 < t_hi) stash(buf ^ 1);
@@ -1237,7 +1283,12 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
-  if (a.head_dim == 128 && global && v_path == 0) {
+  if (a.key_bias) {
+    // additive key bias: the masked kernel, 128-row tiles, any head_dim and window
+    if (a.head_dim == 32) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true, true>), dim3(grid), block, 0, s, a);
+    else if (a.head_dim == 64) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, true, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true, true>), dim3(grid), block, 0, s, a);
+  } else if (a.head_dim == 128 && global && v_path == 0) {
     hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (a.head_dim != kD) {
     // head_dim 32, and the local layers of head_dim 128: the masked kernel covers every

@@ -35,15 +35,17 @@ def run_simple(q32, k32, v32, lens, dtype, scale, window=-1, want_lse=True, stre
     return o.double().cpu().numpy(), (None if lse is None else lse.double().cpu().numpy())
 
 
-def run_ex(q32, k32, v32, lens, dtype, scale, left=-1, right=-1, tuning=0, want_lse=True):
+def run_ex(q32, k32, v32, lens, dtype, scale, left=-1, right=-1, tuning=0, want_lse=True, key_bias=None):
+    """key_bias: None or float32 [B, N] of storage-representable values (inf allowed)."""
     B, H, N, D = q32.shape
     q, k, v = to_dev(q32, dtype), to_dev(k32, dtype), to_dev(v32, dtype)
     o = poison((B, H, N, D), dtype)
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     sl = None if lens is None else torch.as_tensor(np.asarray(lens), dtype=torch.int32).cuda()
+    kb = None if key_bias is None else to_dev(np.ascontiguousarray(key_bias, dtype=np.float32), dtype)
     fa.fa_fwd_ex(dtype=FA_DT[dtype], q=q, k=k, v=v, o=o, lse=lse, seq_lens=sl, batch=B, heads=H,
                  max_len=N, head_dim=D, scale=scale, window_left=left, window_right=right,
-                 tuning=tuning)
+                 tuning=tuning, key_bias=kb)
     torch.cuda.synchronize()
     return o.double().cpu().numpy(), (None if lse is None else lse.double().cpu().numpy())
 

@@ -86,6 +86,9 @@ def test_ex_entry_point_rejects_bad_arguments():
     assert fa.fa_fwd_ex(**{**base, "tuning": 0x3}) == -9
     assert fa.fa_fwd_ex(**{**base, "q_strides": (512, 64, 65)}) == -6
     assert fa.fa_fwd_ex(**{**base, "k_strides": (512, 64, 32)}) == -2
+    assert fa.fa_fwd_ex(**{**base, "key_bias": P + 1}) == -6
+    assert fa.fa_fwd_ex(**{**base, "key_bias": P, "key_bias_stride": 4}) == -2     # shorter than max_len
+    assert fa.fa_fwd_ex(**{**base, "key_bias_stride": -8}) == -2
     assert fa.load_library().fa_fwd_ex(None) == -1
     with pytest.raises(fa.FaError) as e:
         fa.fa_fwd_ex(**{**base, "head_dim": 48, "check": True})

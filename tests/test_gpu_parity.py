@@ -274,6 +274,61 @@ def test_head_dims_longer_sequence_sampled_rows(D):
             assert np.all(o[b, :, n:] == 0) and np.all(np.isneginf(lse[b, :, n:]))
 
 
+# ------------------------------------------------------------------ additive key bias
+def _random_bias(seed, B, N, dtype, holes=True):
+    rng = np.random.default_rng(seed)
+    bias = round_to_storage((rng.standard_normal((B, N)) * 2.0).astype(np.float32), dtype)
+    if holes:   # non-tail key mask: about one key in five excluded
+        bias[rng.random((B, N)) < 0.2] = -np.inf
+    return bias
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("D", [32, 64, 128])
+@pytest.mark.parametrize("left,right", [(-1, -1), (63, 64), (0, 5), (70, -1)])
+def test_key_bias_random_values_and_holes(D, dtype, left, right):
+    """The operator's pad_bias input (paper Sec. 4.1.3, Eq. 1) with arbitrary values and
+    -inf holes, on top of sequence lengths and windows."""
+    B, H, N = 2, 2, 333
+    _, q, k, v = draw(800 + D, B, H, N, D, dtype)
+    lens = [333, 150]
+    bias = _random_bias(801 + D, B, N, dtype)
+    scale = 1.0 / np.sqrt(D)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, left, right, key_bias=bias)
+    o, lse = run_ex(q, k, v, lens, dtype, scale, left, right, key_bias=bias)
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"bias D={D} {dtype} {left},{right}")
+
+
+def test_key_bias_paper_padding_form_equals_seq_lens():
+    """-65504 on the padded keys and no seq_lens (the paper's own input form) gives, on the
+    valid rows, the result of the seq_lens form; a zero bias changes nothing."""
+    B, H, N, D = 2, 3, 200, 64
+    _, q, k, v = draw(810, B, H, N, D, "fp16")
+    lens = [200, 131]
+    bias = np.where(np.arange(N)[None, :] < np.array(lens)[:, None], 0.0, -65504.0).astype(np.float32)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125)
+    o, lse = run_ex(q, k, v, None, "fp16", 0.125, key_bias=bias)
+    for b, n in enumerate(lens):
+        assert np.abs(o[b, :, :n] - o_ref[b, :, :n]).max() <= TOL["fp16"]["max_abs"]
+        assert np.abs(lse[b, :, :n] - lse_ref[b, :, :n]).max() <= LSE_TOL
+    o0, lse0 = run_ex(q, k, v, lens, "fp16", 0.125, key_bias=np.zeros((B, N), dtype=np.float32))
+    o1, lse1 = run_ex(q, k, v, lens, "fp16", 0.125, tuning=fa.FA_TUNE_BM_128)
+    check_against(o0, lse0, o_ref, lse_ref, lens, "fp16", label="zero bias")
+    assert np.abs(o0 - o1).max() <= 1e-3 and np.abs(lse0[:, :, :131] - lse1[:, :, :131]).max() <= 1e-3
+
+
+def test_key_bias_all_keys_excluded_and_large_values():
+    """Every key at -inf: o = 0, lse = -inf, no NaN.  Large biases force reference refreshes."""
+    B, H, N, D = 1, 2, 130, 64
+    _, q, k, v = draw(811, B, H, N, D, "fp16")
+    o, lse = run_ex(q, k, v, None, "fp16", 0.125, key_bias=np.full((B, N), -np.inf, dtype=np.float32))
+    assert np.all(o == 0) and np.all(np.isneginf(lse))
+    bias = round_to_storage((np.arange(N, dtype=np.float32) * 3.0)[None, :], "fp16")   # rising: a refresh per block
+    o_ref, lse_ref = attention_oracle(q, k, v, None, 0.125, key_bias=bias)
+    o, lse = run_ex(q, k, v, None, "fp16", 0.125, key_bias=bias)
+    check_against(o, lse, o_ref, lse_ref, None, "fp16", relative=True, label="rising bias")
+
+
 # ------------------------------------------------------------------ the five named workloads
 @pytest.mark.parametrize("name", ["c1_512", "c2_batch32"])
 def test_named_small_configs_full_compare(name):
