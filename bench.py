@@ -105,6 +105,38 @@ def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0):
     return wall_ms / steps, ev_ms / steps
 
 
+def layer_sequence_time(w, lens, q, k, v, layers=22, every=3, window=128, reps=5):
+    """Attention calls of one pass through a ModernBERT-shaped encoder (paper Sec. 2.4 and
+    4.1.3: local layers with a 128-token window, every third layer global): `layers` calls
+    back to back on the workload's tensors, global when layer % every == 0.  Returns
+    (ms per pass, number of global layers)."""
+    import torch
+    import paper_2603_12646_amd as fa
+
+    tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    qd, kd, vd = (torch.from_numpy(x).to(tdt).cuda() for x in (q, k, v))
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+    sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    fn = fa.fa_fwd if w.dtype == "fp16" else fa.fa_fwd_bf16
+    n_global = len([l for l in range(layers) if l % every == 0])
+
+    def one_pass():
+        for layer in range(layers):
+            fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale,
+               -1 if layer % every == 0 else window)
+
+    one_pass()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(reps):
+        one_pass()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / reps, n_global
+
+
 def measured_ceilings():
     """What this machine sustains with nothing but matrix-core instructions (zero and random
     operands) and with a plain copy: the program built from csrc/ceilings.hip, run as a child
@@ -256,6 +288,15 @@ def main():
                             "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype, "head_dim": ow.head_dim}
             del oq, ok_, ov
         out["config"]["other_workloads"] = others
+        # one encoder pass worth of attention calls (22 layers, every third global) at 8K and 32K
+        seqs = {}
+        for name in ("c3_8k", "c5a_32k_global"):
+            lw = ALL_CONFIGS[name]
+            ll, lq, lk, lv = make_inputs(lw)
+            ms, n_global = layer_sequence_time(lw, ll, lq, lk, lv)
+            seqs[name] = {"layers": 22, "global_layers": n_global, "local_window": 128, "ms_per_pass": ms}
+            del lq, lk, lv
+        out["config"]["layer_sequence"] = seqs
 
     print(json.dumps(out))
 
