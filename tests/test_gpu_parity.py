@@ -274,6 +274,49 @@ def test_head_dims_longer_sequence_sampled_rows(D):
             assert np.all(o[b, :, n:] == 0) and np.all(np.isneginf(lse[b, :, n:]))
 
 
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library allocates nothing, never synchronises and launches on the caller's stream,
+    so a global and a local call can be recorded into a graph; every replay (with eager work
+    and fresh inputs in between) must reproduce the eager result bit for bit."""
+    B, H, N, D = 2, 3, 600, 64
+    lens = [600, 333]
+    sl = torch.tensor(lens, dtype=torch.int32).cuda()
+    qd = torch.zeros((B, H, N, D), dtype=torch.float16, device="cuda")
+    kd, vd = torch.zeros_like(qd), torch.zeros_like(qd)
+    o_g, o_l = poison((B, H, N, D), "fp16"), poison((B, H, N, D), "fp16")
+    lse_g = torch.zeros((B, H, N), dtype=torch.float32, device="cuda")
+    lse_l = torch.zeros_like(lse_g)
+
+    def calls():
+        fa.fa_fwd(qd, kd, vd, o_g, lse_g, B, H, sl, N, D, 0.125, -1)
+        fa.fa_fwd(qd, kd, vd, o_l, lse_l, B, H, sl, N, D, 0.125, 128)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()                     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls()
+    for rep in range(3):
+        _, q, k, v = draw(900 + rep, B, H, N, D, "fp16")
+        qd.copy_(to_dev(q, "fp16")); kd.copy_(to_dev(k, "fp16")); vd.copy_(to_dev(v, "fp16"))
+        o_g.fill_(float("nan")); o_l.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (o_g, lse_g, o_l, lse_l)]
+        o_g.fill_(float("nan")); o_l.fill_(float("nan"))
+        calls()
+        torch.cuda.synchronize()
+        for a_, b_ in zip(got, (o_g, lse_g, o_l, lse_l)):
+            assert torch.equal(a_, b_), f"replay {rep} differs from the eager call"
+        o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125)
+        check_against(got[0].double().cpu().numpy(), got[1].double().cpu().numpy(), o_ref, lse_ref, lens, "fp16",
+                      label=f"graph replay {rep}")
+
+
 # ------------------------------------------------------------------ additive key bias
 def _random_bias(seed, B, N, dtype, holes=True):
     rng = np.random.default_rng(seed)
