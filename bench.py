@@ -137,6 +137,44 @@ def layer_sequence_time(w, lens, q, k, v, layers=22, every=3, window=128, reps=5
     return start.elapsed_time(stop) / reps, n_global
 
 
+def three_sessions_time(reps=10):
+    """The paper deploys three classifier sessions side by side (Sec. 4.1.1, 4.1.3): the three
+    sequences of the 16K workload as three independent calls on three streams, against the
+    same three sequences as one batched call.  Returns (ms concurrent, ms batched)."""
+    import torch
+    import paper_2603_12646_amd as fa
+    from workloads import ALL_CONFIGS, make_inputs
+
+    w = ALL_CONFIGS["c4_16k_x3"]
+    lens, q, k, v = make_inputs(w)
+    tdt = torch.bfloat16
+    qd, kd, vd = (torch.from_numpy(x).to(tdt).cuda() for x in (q, k, v))
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+    sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    streams = [torch.cuda.Stream() for _ in range(w.batch)]     # default priority
+
+    def concurrent():
+        for b, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                fa.fa_fwd_bf16(qd[b:b + 1], kd[b:b + 1], vd[b:b + 1], o[b:b + 1], lse[b:b + 1], 1, w.heads,
+                               sl[b:b + 1], w.max_len, w.head_dim, w.scale, w.window)
+
+    def batched():
+        fa.fa_fwd_bf16(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
+
+    out = []
+    for fn, multi in ((concurrent, True), (batched, False)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) * 1e3 / reps)
+    return out[0], out[1]
+
+
 def measured_ceilings():
     """What this machine sustains with nothing but matrix-core instructions (zero and random
     operands) and with a plain copy: the program built from csrc/ceilings.hip, run as a child
@@ -305,6 +343,8 @@ def main():
             seqs[name] = {"layers": 22, "global_layers": n_global, "local_window": 128, "ms_per_pass": ms}
             del lq, lk, lv
         out["config"]["layer_sequence"] = seqs
+        conc_ms, batch_ms = three_sessions_time()
+        out["config"]["three_sessions_16k"] = {"three_streams_ms": conc_ms, "one_batched_call_ms": batch_ms}
 
     print(json.dumps(out))
 

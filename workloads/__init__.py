@@ -97,6 +97,7 @@ def draw(seed, batch, heads, max_len, head_dim, dtype, qk_gain=1.0, random_lens=
 NEXT_CONFIGS = {
     "d128_8k": Workload("d128_8k", 5, "fp16", 1, 8, 8192, 128, 128 ** -0.5, -1, (7900,), qk_gain=1.5),
     "d128_32k": Workload("d128_32k", 6, "bf16", 1, 8, 32768, 128, 128 ** -0.5, -1, None),
+    "d128_32k_local": Workload("d128_32k_local", 6, "bf16", 1, 8, 32768, 128, 128 ** -0.5, 128, None),
 }
 ALL_CONFIGS = {**CONFIGS, **NEXT_CONFIGS}
 
