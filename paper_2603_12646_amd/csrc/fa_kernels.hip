@@ -301,15 +301,17 @@ __device__ __forceinline__ void prob_block(const floatx16& sv, float c, float mc
   blk = l0 + l1;
 }
 
-// Visibility bits of a lane's 16 accumulator elements for the block starting at key kb0.
+// Visibility bits of a lane's 16 accumulator elements for the block starting at key kb0:
+// bit r is set iff jlo <= kb0 + 8*(r/4) + 4*hh + r%4 <= jhi.  Built from one 32-bit range
+// mask (bit k = key kb0 + 4*hh + k visible) whose nibbles 0, 2, 4, 6 are the lane's keys.
 __device__ __forceinline__ uint32_t visible_bits(int kb0, int hh, int jlo, int jhi) {
-  uint32_t vis = 0;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int jg = kb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-    vis |= (jg >= jlo && jg <= jhi) ? (1u << r) : 0u;
-  }
-  return vis;
+  int lo = jlo - kb0 - 4 * hh, hi = jhi - kb0 - 4 * hh;
+  lo = lo < 0 ? 0 : lo;
+  hi = hi > 31 ? 31 : hi;
+  const bool none = hi < lo;                          // also covers hi < 0 and lo > 31
+  const int lo_s = lo > 31 ? 31 : lo, hi_s = hi < 0 ? 0 : hi;  // shift counts stay in 0..31
+  const uint32_t m = none ? 0u : ((0xFFFFFFFFu >> (31 - hi_s)) & (0xFFFFFFFFu << lo_s));
+  return (m & 0xFu) | ((m >> 4) & 0xF0u) | ((m >> 8) & 0xF00u) | ((m >> 12) & 0xF000u);
 }
 
 // One 32-key block, scores to accumulator, with per-element masking if MASKED.
@@ -855,13 +857,29 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
     const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ k_swz(dl_r)) * 8);
     const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ v_swz(dl_r)) * 8);
     const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
+    if (b_hi * 32 <= N) {
+      // every row exists: one per-lane offset, the block base advances in scalar registers
+      const uint32_t klane = (uint32_t)dl_r * krow_b + kchunk, vlane = (uint32_t)dl_r * vrow_b + vchunk;
+      const uint16_t* kg = kp + (int64_t)b_lo * 32 * a.ks[2];
+      const uint16_t* vg = vp + (int64_t)b_lo * 32 * a.vs[2];
 #pragma unroll
-    for (int i = 0; i < kResBlocks; ++i) {
-      if (b_lo + i < b_hi) {
-        const int jg = (b_lo + i) * 32 + dl_r;
-        const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
-        load16_to_lds(kp, jc * krow_b + kchunk, &lds_k[i * kBlk + 8 * wave * kD]);
-        load16_to_lds(vp, jc * vrow_b + vchunk, &lds_v[i * kBlk + 8 * wave * kD]);
+      for (int i = 0; i < kResBlocks; ++i) {
+        if (b_lo + i < b_hi) {
+          load16_to_lds(kg, klane, &lds_k[i * kBlk + 8 * wave * kD]);
+          load16_to_lds(vg, vlane, &lds_v[i * kBlk + 8 * wave * kD]);
+          kg += 32 * a.ks[2];
+          vg += 32 * a.vs[2];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < kResBlocks; ++i) {
+        if (b_lo + i < b_hi) {
+          const int jg = (b_lo + i) * 32 + dl_r;
+          const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+          load16_to_lds(kp, jc * krow_b + kchunk, &lds_k[i * kBlk + 8 * wave * kD]);
+          load16_to_lds(vp, jc * vrow_b + vchunk, &lds_v[i * kBlk + 8 * wave * kD]);
+        }
       }
     }
   }
