@@ -948,14 +948,24 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
       uint32_t pk[8];
       float blk;
       uint32_t vis = 0xFFFFu;
-      if (interior) {
-        prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
-      } else {
-        vis = visible_bits(kb0, hh, jlo, jhi);
-        prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+      if (!interior) vis = visible_bits(kb0, hh, jlo, jhi);
+      // Rows that have not seen a key yet (the wavefront's first block, and the odd row whose
+      // window starts a block later) adopt this block's maximum as their reference.  Nothing
+      // has been accumulated for such a row, so there is nothing to rescale.
+      if (__any(alive && st.m_ref[0] == -INFINITY)) {
+        float t0 = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+        const float tmax = max_xor32(t0);
+        if (st.m_ref[0] == -INFINITY) {
+          st.m_ref[0] = tmax;
+          st.mc[0] = tmax == -INFINITY ? 0.f : tmax * c;
+        }
       }
-      // !(blk <= limit) also catches a NaN sum; no reference yet = first visible block
-      const bool trig = alive && (!(blk <= kPLimit) || st.m_ref[0] == -INFINITY);
+      if (interior) prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
+      else prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+      // !(blk <= limit) also catches a NaN sum
+      const bool trig = alive && !(blk <= kPLimit);
       if (__any(trig)) {
         // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
         const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
