@@ -414,3 +414,22 @@ def test_named_large_configs_sampled_rows(name):
             assert np.abs(lse[b, h, rows] - lse_ref).max() <= LSE_TOL, (name, b, h)
     print(f"{name}: max-abs {worst:.3e} mean-abs {total / count:.3e} over {count} sampled outputs")
     assert worst <= tol["max_abs"] and total / count <= tol["mean_abs"]
+
+
+# ------------------------------------------------------------------ measurement helper program
+def test_ceilings_program_reports_plausible_numbers():
+    """The standalone program bench.py runs for its `ceilings` block: matrix-core rate with
+    zero and with random operands, and a 1 GiB copy."""
+    import json
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(fa.LIB_PATH), "fa_ceilings")
+    assert os.path.exists(exe), "fa_ceilings not built (python -m paper_2603_12646_amd.build)"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    d = json.loads(r.stdout.strip().splitlines()[-1])
+    for key in ("mfma_f16_zero_tflops", "mfma_f16_random_tflops", "mfma_bf16_zero_tflops",
+                "mfma_bf16_random_tflops", "copy_gbs"):
+        assert d[key] > 0
+    assert 500 < d["mfma_f16_random_tflops"] <= d["mfma_f16_zero_tflops"] * 1.05 < 2500 * 1.1
+    assert 1000 < d["copy_gbs"] < 8000
