@@ -179,6 +179,30 @@ def test_strided_inputs_bshd_and_packed_qkv(dtype):
     check_against(o_np, lse.double().cpu().numpy(), o_ref, lse_ref, lens, dtype, relative=True, label="strided")
 
 
+@pytest.mark.parametrize("D,left,right", [(128, -1, -1), (128, 10, 20), (32, -1, -1)])
+def test_strided_inputs_other_head_dims(D, left, right):
+    """Packed QKV read in place for head_dim 128 (pipelined global kernel and masked kernel)
+    and head_dim 32."""
+    B, H, N = 2, 2, 260
+    _, q, k, v = draw(307 + D, B, H, N, D, "bf16")
+    lens = [260, 77]
+    scale = 1.0 / np.sqrt(D)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, left, right)
+    packed = np.stack([q, k, v], axis=0).transpose(1, 3, 0, 2, 4).copy()  # B, N, 3, H, D
+    dev = to_dev(packed, "bf16")
+    o = poison((B, N, H, D), "bf16")
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    sl = torch.tensor(lens, dtype=torch.int32).cuda()
+    st = (N * 3 * H * D, D, 3 * H * D)
+    fa.fa_fwd_ex(dtype=FA_DT["bf16"], q=dev[:, :, 0].data_ptr(), k=dev[:, :, 1].data_ptr(),
+                 v=dev[:, :, 2].data_ptr(), o=o, lse=lse, seq_lens=sl, batch=B, heads=H, max_len=N,
+                 head_dim=D, scale=scale, window_left=left, window_right=right, q_strides=st,
+                 k_strides=st, v_strides=st, o_strides=(N * H * D, D, H * D))
+    torch.cuda.synchronize()
+    o_np = o.double().cpu().numpy().transpose(0, 2, 1, 3)
+    check_against(o_np, lse.double().cpu().numpy(), o_ref, lse_ref, lens, "bf16", relative=True, label=f"strided D={D}")
+
+
 def test_valid_call_returns_zero_and_bad_call_leaves_output_untouched():
     B, H, N, D = 1, 1, 64, 64
     _, q, k, v = draw(306, B, H, N, D, "fp16")
