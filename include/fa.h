@@ -137,8 +137,10 @@ typedef struct fa_params {
      key_bias[b, j] is added to scale * q_i.k_j for every head and query (it is not
      multiplied by scale); -infinity excludes key j, so any key mask can be expressed,
      and the paper's -65504 on padded keys works as written.  It applies on top of
-     seq_lens and the window.  2-byte alignment.  A call with a key bias runs the
-     general (masked) kernel. */
+     seq_lens and the window.  2-byte alignment.  Global layers of head_dim 64 / 128
+     keep the pipelined kernel (the bias enters through the score product's
+     accumulator input); local layers, head_dim 32 and scale == 0 take the general
+     (masked) kernel. */
   const void* key_bias;
   int64_t key_bias_stride; /* elements between batch rows; 0 = max_len; >= max_len */
 } fa_params;

@@ -81,7 +81,10 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
 
   // head_dim 32 and 128 run the 128-row kernel only (the tile-size hint is ignored there)
-  const int bm = (p->head_dim != 64 || p->key_bias) ? 128
+  // ... and so does a key bias unless it can ride on the pipelined global kernel
+  const bool windowed = p->window_left >= 0 || p->window_right >= 0;
+  const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
+  const int bm = (p->head_dim != 64 || bias_on_masked_kernel) ? 128
                                    : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
   const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
   const int64_t total = n_qtiles * p->batch * p->heads;
@@ -93,6 +96,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len; a.head_dim = p->head_dim;
   a.key_bias = p->key_bias;
   a.kb_stride = p->key_bias_stride ? p->key_bias_stride : p->max_len;
+  a.inv_abs_scale = p->scale != 0.0f ? 1.0f / std::fabs(p->scale) : 0.0f;
   const float c = std::fabs(p->scale) * kLog2e;
   a.c = c;
   a.negate_q = std::signbit(p->scale) && p->scale != 0.0f ? 1 : 0;

@@ -11,6 +11,7 @@ struct FaKernelArgs {
   const int32_t* seq_lens;  // device, may be null
   const void* key_bias;     // device, [batch][kb_stride] 16-bit values, may be null
   int64_t kb_stride;        // elements between batch rows of key_bias
+  float inv_abs_scale;      // 1 / |scale| (0 when scale is 0): key bias in raw-score units
   int32_t batch, heads, max_len;
   int32_t head_dim;         // 32, 64 or 128
   int64_t qs[3], ks[3], vs[3], os[3];  // element strides: batch, head, row

@@ -322,11 +322,14 @@ __device__ __forceinline__ uint32_t visible_bits(int kb0, int hh, int jlo, int j
 //
 // bias2 (optional): 32 floats in LDS, the block's additive key bias times log2(e).  With a
 // bias the row state is kept in the log2 domain (m_ref = mc = reference of s*c + bias2).
+// bias_raw (optional, instead of bias2): 32 floats in LDS, the bias divided by |scale|; it
+// is simply added to the raw scores and everything else stays in raw-score units.
 template <class T, int NQB, bool MASKED, int FRAG, int D>
 __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typename T::v8 (&qreg)[NQB][D / 16],
                                              const uint16_t* kblk, const uint16_t* vblk, int kb0,
                                              const int (&jlo)[NQB], const int (&jhi)[NQB], int lane,
-                                             float c, float tau_raw, const float* bias2 = nullptr) {
+                                             float c, float tau_raw, const float* bias2 = nullptr,
+                                             const float* bias_raw = nullptr) {
   const int l32 = lane & 31, hh = lane >> 5;
   floatx16 sacc[NQB];
 #pragma unroll
@@ -339,6 +342,19 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
     const typename T::v8 ka = FRAG == 2 ? load_k_frag_swz<T>(kblk, l32, hh, ks) : load_k_frag<T, D>(kblk, l32, hh, ks);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) sacc[qb] = T::mfma(ka, qreg[qb][ks], sacc[qb]);
+  }
+  if (bias_raw) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 b4 = *(const float4*)&bias_raw[8 * g + 4 * hh];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        sacc[qb][4 * g + 0] += b4.x;
+        sacc[qb][4 * g + 1] += b4.y;
+        sacc[qb][4 * g + 2] += b4.z;
+        sacc[qb][4 * g + 3] += b4.w;
+      }
+    }
   }
   uint32_t pk[NQB][8];
 #pragma unroll
@@ -1005,7 +1021,11 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 // ======================================================================================
 // Global kernel: software pipeline over the full tiles + masked ragged tail
 // ======================================================================================
-template <class T, int D, int NQB, int WAVES_PER_EU>
+// BIAS: the additive key bias rides on the score product: the bias of a key block, divided
+// by |scale|, is the C operand of the block's first MFMA, so the scores arrive with the bias
+// already in them and the vector work is unchanged.  Bias values are staged per K tile
+// through a register of wavefront 0 into a small LDS array with the tile's two stages.
+template <class T, int D, int NQB, int WAVES_PER_EU, bool BIAS = false>
 __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
   static_assert(D == 64 || D == 128, "pipelined kernel: head_dim 64 or 128");
   constexpr int BM = kWaves * 32 * NQB;
@@ -1018,6 +1038,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   static_assert(2 * kBN * SV >= 96 * SV && 2 * kBN * SK >= kWaves * epi_patch(D), "tail and epilogue reuse the stages");
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * SK];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * SV];
+  __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? 2 * kBN : 4];  // [stage][tile row], bias / |scale|
 
   TileCoord tc;
   if (!locate_tile<BM>(a, tc)) return;
@@ -1032,6 +1053,12 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
   uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
   float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+  const uint16_t* bp = BIAS ? (const uint16_t*)a.key_bias + tc.b * a.kb_stride : nullptr;
+  // bias of key j in raw-score units (index clamped: keys outside [0, n) are never used unmasked)
+  auto bias_of = [&](int j) {
+    j = j < 0 ? 0 : (j < N ? j : N - 1);
+    return T::to_float(bp[j]) * a.inv_abs_scale;
+  };
 
   if (q0 >= n) {
     zero_fill<BM, D>(a, tc, op, lsep);
@@ -1141,6 +1168,20 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // pipeline registers: scores of the current / next unit, packed probabilities of the
   // previous / current unit, operand fragments of the key block in flight
   floatx16 sA, sB;
+  floatx16 bcur;  // BIAS: the bias of the key block whose K fragments are in ka (C layout)
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bcur[r] = 0.f;
+  auto bias_frag = [&](const float* bblk) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 b4 = *(const float4*)&bblk[8 * g + 4 * hh];
+      bcur[4 * g + 0] = b4.x;
+      bcur[4 * g + 1] = b4.y;
+      bcur[4 * g + 2] = b4.z;
+      bcur[4 * g + 3] = b4.w;
+    }
+  };
+  float bst = 0.f;  // BIAS: wavefront 0 carries the next tile's bias from its load to its LDS write
   typename T::v8 pA[2], pB[2], ka[KS], va[2][DB];
   pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
 #pragma unroll
@@ -1150,10 +1191,19 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     // prologue: unit (0,0)'s scores need K rows [0, 32): tile "-1" (rows [-32, 32), clamped)
     fetch(-1, &lds_k[kBN * D], &lds_v[kBN * D]);
     fetch(0, lds_k, lds_v);
+    if (BIAS && wave == 0) {
+      // tile -1 (keys -32..31) into stage 1, tile 0 (keys 32..95) into stage 0
+      lds_bias[kBN + lane] = bias_of(lane - 32);
+      lds_bias[lane] = bias_of(lane + 32);
+    }
     wait_direct_loads();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) sA[r] = 0.f;
+    if (BIAS) {
+      bias_frag(&lds_bias[kBN + 32]);
+      sA = bcur;
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       ka[ks] = k_frag(&lds_k[kBN * D + 32 * D], ks);
@@ -1174,7 +1224,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
     // fragments already in registers are reused.
     auto unit = [&](auto QBc, auto NQc, auto PQc, auto LOADc, floatx16& s_cur, floatx16& s_nxt,
                     typename T::v8 (&p_prev)[2], typename T::v8 (&p_cur)[2], const uint16_t* kblk,
-                    const uint16_t* vblk) {
+                    const uint16_t* vblk, const float* bblk) {
       constexpr int QB = decltype(QBc)::value, NQ = decltype(NQc)::value, PQ = decltype(PQc)::value;
       constexpr bool LOAD = decltype(LOADc)::value;
       if (LOAD) {
@@ -1182,9 +1232,15 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         for (int ks = 0; ks < KS; ++ks) ka[ks] = k_frag(kblk, ks);
 #pragma unroll
         for (int i = 0; i < 2 * DB; ++i) va[i / DB][i % DB] = vt_frag(vblk, i / DB, i % DB);
+        if (BIAS) bias_frag(bblk);
       }
+      // the first product of the score block takes the bias (or zero) as its C operand
+      if (BIAS) {
+        s_nxt = bcur;
+      } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+        for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+      }
       // dependent products (the k-steps of a score block, the two of an output block)
       // alternate with independent ones
 #pragma unroll
@@ -1221,20 +1277,26 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       constexpr int STAGE = decltype(STAGEc)::value;
       const uint16_t* kt = &lds_k[STAGE * kBN * D];
       const uint16_t* vt = &lds_v[STAGE * kBN * D];
+      const float* bt = &lds_bias[BIAS ? STAGE * kBN : 0];
       // the stage being filled was last read in iteration t-1; every wavefront is past
       // that iteration's barrier
-      if (t + 1 < nf) fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * D], &lds_v[(STAGE ^ 1) * kBN * D]);
+      if (t + 1 < nf) {
+        fetch_next(t + 2 == nf, &lds_k[(STAGE ^ 1) * kBN * D], &lds_v[(STAGE ^ 1) * kBN * D]);
+        if (BIAS && wave == 0) bst = bias_of((t + 1) * kBN + 32 + lane);
+      }
       if (wave_has_rows) {
         if constexpr (NQB == 1) {
-          unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D);
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sA, sB, pA, pB, kt, vt, bt);
+          unit(I0{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D, bt + 32);
         } else {
-          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt, vt);
-          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt);
-          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D);
+          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt, bt);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt, vt, bt);
+          unit(I0{}, I1{}, I1{}, std::false_type{}, sA, sB, pA, pB, kt, vt, bt);
+          unit(I1{}, I0{}, I0{}, std::true_type{}, sB, sA, pB, pA, kt + 32 * D, vt + 32 * D, bt + 32);
         }
       }
+      // the other bias stage was last read in iteration t-1
+      if (BIAS && wave == 0 && t + 1 < nf) lds_bias[(STAGE ^ 1) * kBN + lane] = bst;
       wait_direct_loads();  // this wavefront's share of the next tile has landed
       __syncthreads();
     };
@@ -1267,6 +1329,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         const int jc = jg < N ? jg : N - 1;
         *(uint4*)&lds_k[row * SK + c8] = *(const uint4*)(kp + jc * a.ks[2] + c8);
       }
+      if (BIAS && wave == 0) lds_bias[lane] = bias_of(base + lane);  // every stage is free after the loop
     }
   }
   __syncthreads();
@@ -1294,7 +1357,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
         const int kb0 = nf * kBN + kb * 32;
         if (kb0 >= n) continue;
         simple_block<T, NQB, true, 0>(st, qreg, &lds_k[kb * 32 * SK], &lds_v[(32 + kb * 32) * SV], kb0,
-                                      jlo, jhi, lane, c, tau_raw);
+                                      jlo, jhi, lane, c, tau_raw, nullptr, BIAS ? &lds_bias[kb * 32] : nullptr);
       }
     }
   }
@@ -1311,8 +1374,13 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
-  if (a.key_bias) {
-    // additive key bias: the masked kernel, 128-row tiles, any head_dim and window
+  if (a.key_bias && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
+    // additive key bias on a global layer: the pipelined kernel with the bias as MFMA C operand
+    if (a.head_dim == 128) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2, true>), dim3(grid), block, 0, s, a);
+    else if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2, true>), dim3(grid), block, 0, s, a);
+    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2, true>), dim3(grid), block, 0, s, a);
+  } else if (a.key_bias) {
+    // additive key bias otherwise: the masked kernel, 128-row tiles, any head_dim and window
     if (a.head_dim == 32) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true, true>), dim3(grid), block, 0, s, a);
     else if (a.head_dim == 64) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, true, true>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true, true>), dim3(grid), block, 0, s, a);

@@ -350,20 +350,54 @@ def _random_bias(seed, B, N, dtype, holes=True):
     return bias
 
 
+@pytest.mark.parametrize("tuning", [0, fa.FA_TUNE_BM_256, fa.FA_TUNE_V_SCALAR])
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 @pytest.mark.parametrize("D", [32, 64, 128])
 @pytest.mark.parametrize("left,right", [(-1, -1), (63, 64), (0, 5), (70, -1)])
-def test_key_bias_random_values_and_holes(D, dtype, left, right):
+def test_key_bias_random_values_and_holes(D, dtype, left, right, tuning):
     """The operator's pad_bias input (paper Sec. 4.1.3, Eq. 1) with arbitrary values and
-    -inf holes, on top of sequence lengths and windows."""
+    -inf holes, on top of sequence lengths and windows.  Global layers of head_dim 64 / 128
+    take the pipelined kernel (128- and 256-row tiles), everything else the masked kernel."""
     B, H, N = 2, 2, 333
     _, q, k, v = draw(800 + D, B, H, N, D, dtype)
     lens = [333, 150]
     bias = _random_bias(801 + D, B, N, dtype)
     scale = 1.0 / np.sqrt(D)
     o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, left, right, key_bias=bias)
-    o, lse = run_ex(q, k, v, lens, dtype, scale, left, right, key_bias=bias)
-    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"bias D={D} {dtype} {left},{right}")
+    o, lse = run_ex(q, k, v, lens, dtype, scale, left, right, tuning=tuning, key_bias=bias)
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"bias D={D} {dtype} {left},{right} {tuning}")
+
+
+@pytest.mark.parametrize("N", [1, 31, 33, 64, 65, 127, 129, 257, 640])
+@pytest.mark.parametrize("D", [64, 128])
+def test_key_bias_global_lengths_around_tile_edges(D, N):
+    """Pipelined kernel with a bias: prologue only, tail only, several tiles plus a tail;
+    negative scale and scale 0 as well (scale 0 falls back to the masked kernel)."""
+    B, H = 2, 2
+    _, q, k, v = draw(820 + N + D, B, H, N, D, "fp16")
+    bias = _random_bias(821 + N, B, N, "fp16", holes=N > 4)
+    lens = [N, max(1, N - 7)]
+    for scale in (0.11, -0.2, 0.0):
+        o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, key_bias=bias)
+        o, lse = run_ex(q, k, v, lens, "fp16", scale, key_bias=bias)
+        check_against(o, lse, o_ref, lse_ref, lens, "fp16", relative=True, label=f"bias D={D} N={N} scale={scale}")
+
+
+def test_key_bias_8k_sampled_rows():
+    """The 8K workload with a random key mask (one key in ten excluded) and small biases."""
+    w = CONFIGS["c3_8k"]
+    lens, q, k, v = make_inputs(w)
+    rng = np.random.default_rng(5)
+    bias = round_to_storage((rng.standard_normal((w.batch, w.max_len)) * 0.5).astype(np.float32), w.dtype)
+    bias[rng.random((w.batch, w.max_len)) < 0.1] = -np.inf
+    o, lse = run_ex(q, k, v, lens, w.dtype, w.scale, key_bias=bias)
+    n = int(lens[0])
+    assert np.all(o[0, :, n:] == 0) and np.all(np.isneginf(lse[0, :, n:]))
+    for h in (0, 5, 11):
+        rows = sample_rows(n, rng, 200)
+        o_ref, lse_ref = attention_oracle_rows(q, k, v, 0, h, rows, n, w.scale, key_bias=bias)
+        assert np.abs(o[0, h, rows] - o_ref).max() <= TOL[w.dtype]["max_abs"]
+        assert np.abs(lse[0, h, rows] - lse_ref).max() <= LSE_TOL
 
 
 def test_key_bias_paper_padding_form_equals_seq_lens():
