@@ -138,9 +138,9 @@ typedef struct fa_params {
      multiplied by scale); -infinity excludes key j, so any key mask can be expressed,
      and the paper's -65504 on padded keys works as written.  It applies on top of
      seq_lens and the window.  2-byte alignment.  Global layers of head_dim 64 / 128
-     keep the pipelined kernel (the bias enters through the score product's
-     accumulator input); local layers, head_dim 32 and scale == 0 take the general
-     (masked) kernel. */
+     and the resident local-layer kernel keep their pipelines (the bias enters through
+     the score product's accumulator input); wider or one-sided windows, head_dim 32
+     and scale == 0 take the general (masked) kernel. */
   const void* key_bias;
   int64_t key_bias_stride; /* elements between batch rows; 0 = max_len; >= max_len */
 } fa_params;

@@ -831,12 +831,15 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
 // ======================================================================================
 constexpr int kResBlocks = 8;
 
-template <class T>
+template <class T, bool BIAS = false>
 __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32;
   constexpr int kBlk = 32 * kD;  // elements per block
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[kResBlocks * kBlk];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[kResBlocks * kBlk];
+  // BIAS: additive key bias / |scale| of every resident key; it enters the scores as the C
+  // operand of each block's first MFMA
+  __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? kResBlocks * 32 : 4];
 
   TileCoord tc;
   if (!locate_tile<BM>(a, tc)) return;
@@ -900,6 +903,13 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
     }
   }
 
+  if (BIAS) {
+    // one value per thread: key b_lo*32 + tid (256 resident keys, 256 threads)
+    const uint16_t* bp = (const uint16_t*)a.key_bias + tc.b * a.kb_stride;
+    const int jg = b_lo * 32 + tid;
+    lds_bias[tid] = T::to_float(bp[jg < N ? jg : N - 1]) * a.inv_abs_scale;
+  }
+
   const int qw0 = q0 + wave * 32;
   const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
   const bool wave_has_rows = qw_last >= qw0;
@@ -932,8 +942,23 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
     floatx16 sA, sB;
     typename T::v8 pA[2], pB[2];
     pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+    // accumulator input of a block's score product: its bias, or zero
+    auto score_init = [&](floatx16& sv, int slot) {
+      if (BIAS) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sA[r] = 0.f;
+        for (int g = 0; g < 4; ++g) {
+          const float4 b4 = *(const float4*)&lds_bias[slot * 32 + 8 * g + 4 * hh];
+          sv[4 * g + 0] = b4.x;
+          sv[4 * g + 1] = b4.y;
+          sv[4 * g + 2] = b4.z;
+          sv[4 * g + 3] = b4.w;
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sv[r] = 0.f;
+      }
+    };
+    score_init(sA, fb - b_lo);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
       sA = T::mfma(load_k_frag_swz<T>(&lds_k[(fb - b_lo) * kBlk], l32, hh, ks), qreg[0][ks], sA);
@@ -951,8 +976,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
       for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag_swz<T>(kblk, l32, hh, ks);
 #pragma unroll
       for (int i = 0; i < 4; ++i) va[i] = load_vt_frag_swz<T>(vblk, lane, i >> 1, i & 1);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+      score_init(s_nxt, un - b_lo);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         s_nxt = T::mfma(ka[ks], qreg[0][ks], s_nxt);
@@ -1374,7 +1398,13 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
-  if (a.key_bias && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
+  // 32-key blocks a 128-row query tile of a two-sided window can touch (tiles start at multiples of 128)
+  const int win_blocks = (a.wl >= 0 && a.wr >= 0) ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+  if (a.key_bias && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
+      win_blocks <= kResBlocks) {
+    // additive key bias on a local layer whose key range stays resident in LDS
+    hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T, true>), dim3(grid), block, 0, s, a);
+  } else if (a.key_bias && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
     // additive key bias on a global layer: the pipelined kernel with the bias as MFMA C operand
     if (a.head_dim == 128) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2, true>), dim3(grid), block, 0, s, a);
     else if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2, true>), dim3(grid), block, 0, s, a);
@@ -1400,10 +1430,7 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2>), dim3(grid), block, 0, s, a);
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
-    // 32-key blocks a 128-row query tile can touch (tiles start at multiples of 128)
-    const bool two_sided = a.wl >= 0 && a.wr >= 0;
-    const int blocks = two_sided ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
-    if (blocks <= kResBlocks) hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T>), dim3(grid), block, 0, s, a);
+    if (win_blocks <= kResBlocks) hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
   } else if (bm == 256) {
     if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 2, true>), dim3(grid), block, 0, s, a);
