@@ -74,8 +74,6 @@ constexpr int kThreads = kWaves * 64;
 // transpose load, 4 rows x 32 bytes per 16 lanes.
 constexpr int stride_k(int D) { return D + 8; }
 constexpr int stride_v(int D) { return D + 16; }
-constexpr int kSK = stride_k(kD);
-constexpr int kSV = stride_v(kD);
 constexpr float kLn2 = 0.693147180559945309f;
 // A lane's 16 probabilities of one block may sum to at most this (against the row's
 // current reference) before the reference is refreshed.  2^14 keeps every single p
