@@ -342,9 +342,9 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
 
 
 # ------------------------------------------------------------------ additive key bias
-def _random_bias(seed, B, N, dtype, holes=True):
+def _random_bias(seed, B, N, dtype, holes=True, gain=2.0):
     rng = np.random.default_rng(seed)
-    bias = round_to_storage((rng.standard_normal((B, N)) * 2.0).astype(np.float32), dtype)
+    bias = round_to_storage((rng.standard_normal((B, N)) * gain).astype(np.float32), dtype)
     if holes:   # non-tail key mask: about one key in five excluded
         bias[rng.random((B, N)) < 0.2] = -np.inf
     return bias
@@ -374,13 +374,17 @@ def test_key_bias_global_lengths_around_tile_edges(D, N):
     """Pipelined kernel with a bias: prologue only, tail only, several tiles plus a tail;
     negative scale and scale 0 as well (scale 0 falls back to the masked kernel)."""
     B, H = 2, 2
-    _, q, k, v = draw(820 + N + D, B, H, N, D, "fp16")
-    bias = _random_bias(821 + N, B, N, "fp16", holes=N > 4)
-    lens = [N, max(1, N - 7)]
-    for scale in (0.11, -0.2, 0.0):
-        o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, key_bias=bias)
-        o, lse = run_ex(q, k, v, lens, "fp16", scale, key_bias=bias)
-        check_against(o, lse, o_ref, lse_ref, lens, "fp16", relative=True, label=f"bias D={D} N={N} scale={scale}")
+    for dtype in ("fp16", "bf16"):
+        _, q, k, v = draw(820 + N + D, B, H, N, D, dtype)
+        # bf16: a milder bias, so that outputs stay well below 1 in magnitude (a bf16 output of
+        # magnitude 1 is by itself 1e-3 away from the exact value on average)
+        bias = _random_bias(821 + N, B, N, dtype, holes=N > 4, gain=2.0 if dtype == "fp16" else 0.5)
+        lens = [N, max(1, N - 7)]
+        for scale in (0.11, -0.2, 0.0):
+            o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, key_bias=bias)
+            o, lse = run_ex(q, k, v, lens, dtype, scale, key_bias=bias)
+            check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True,
+                          label=f"bias {dtype} D={D} N={N} scale={scale}")
 
 
 def test_key_bias_8k_sampled_rows():
