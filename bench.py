@@ -248,7 +248,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
-              "(the path shards by (batch, head) with no exchange; see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by (batch, head) with no exchange)", file=sys.stderr)
         sys.exit(2)
 
     import torch
