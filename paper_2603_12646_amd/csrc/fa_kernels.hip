@@ -572,7 +572,8 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB, D>
 // Masked kernel: windows (and any tile that needs per-element masks)
 // ======================================================================================
 template <class T, int D, int NQB, bool V_TR, bool BIAS = false>
-__global__ __launch_bounds__(kThreads) void fa_fwd_masked_kernel(const FaKernelArgs a) {
+// (two wavefronts per SIMD asked for where the compiler would otherwise settle for one)
+__global__ __launch_bounds__(kThreads, ((D == 128 && !BIAS) || NQB == 2) ? 2 : 1) void fa_fwd_masked_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32 * NQB;
   constexpr int SK = stride_k(D), SV = stride_v(D);
   static_assert(2 * kBN * SK >= kWaves * epi_patch(D), "the K stages double as the epilogue patches");
