@@ -19,7 +19,9 @@
  * The arguments mirror the paper's operator contract (Sec. 4.1.3: inputs
  * Q, K, V and a 1-D padding description, attributes scale, window_size_left,
  * window_size_right, execution on the caller's HIP stream, run-time dispatch on
- * head_dim).
+ * head_dim 32 / 64 / 128).  fa_fwd and fa_fwd_bf16 describe the padding by sequence
+ * lengths; fa_fwd_ex also accepts the operator's additive 1-D key bias (Eq. 1).
+ * Every call can be recorded into a HIP graph.
  *
  * Memory and layout
  *   q, k, v, o : DEVICE pointers, [batch, heads, max_len, head_dim] row-major
