@@ -175,6 +175,91 @@ def three_sessions_time(reps=10):
     return out[0], out[1]
 
 
+def concurrent_requests_time(levels=(10, 20), reps=20):
+    """The paper's steady state after prompt compression is many 512-token requests in flight
+    at once (Sec. 5, concurrency table: C = 10 and 20): C independent calls of the 512-token
+    workload's shape, (a) each on a stream of its own, (b) back to back on one stream, (c) as
+    one batched call.  Host launch time is part of all three.  Returns {C: {...ms}}."""
+    import torch
+    import paper_2603_12646_amd as fa
+    from workloads import ALL_CONFIGS, make_inputs
+
+    w = ALL_CONFIGS["c1_512"]
+    _, q, k, v = make_inputs(w)
+    out = {}
+    for c in levels:
+        tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+        fn = fa.fa_fwd if w.dtype == "fp16" else fa.fa_fwd_bf16
+        qd, kd, vd = (torch.from_numpy(np.repeat(x, c, axis=0)).to(tdt).cuda() for x in (q, k, v))
+        o = torch.empty_like(qd)
+        lse = torch.empty((c, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+        sl = torch.full((c,), w.max_len, dtype=torch.int32, device="cuda")
+        streams = [torch.cuda.Stream() for _ in range(c)]   # default priority
+
+        views = [(qd[b:b + 1], kd[b:b + 1], vd[b:b + 1], o[b:b + 1], lse[b:b + 1], sl[b:b + 1]) for b in range(c)]
+
+        def one(b, stream=None):
+            qb, kb, vb, ob, lb, sb = views[b]
+            fn(qb, kb, vb, ob, lb, 1, w.heads, sb, w.max_len, w.head_dim, w.scale, w.window, stream=stream)
+
+        def own_streams():
+            for b, st in enumerate(streams):
+                one(b, st)
+
+        def one_stream():
+            for b in range(c):
+                one(b)
+
+        def batched():
+            fn(qd, kd, vd, o, lse, c, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
+
+        res = {}
+        for name, f in (("own_streams_ms", own_streams), ("one_stream_ms", one_stream), ("one_batched_call_ms", batched)):
+            f()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                f()
+            torch.cuda.synchronize()
+            res[name] = round((time.perf_counter() - t0) * 1e3 / reps, 4)
+        out[str(c)] = res
+        del qd, kd, vd, o, lse
+    return out
+
+
+def co_location_time(reps=30):
+    """The router shares its GPU with the LLM serving instances (paper Sec. 1, Sec. 4.1.1): the
+    8K workload on a stream that may use all 256 compute units, and on one limited to 128.
+    Returns {units: ms per call}, host launch time included."""
+    import torch
+    import paper_2603_12646_amd as fa
+    from paper_2603_12646_amd.cu_mask import CuMaskedStream, first_units
+    from workloads import ALL_CONFIGS, make_inputs
+
+    w = ALL_CONFIGS["c3_8k"]
+    lens, q, k, v = make_inputs(w)
+    qd, kd, vd = (torch.from_numpy(x).to(torch.float16).cuda() for x in (q, k, v))
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+    sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    torch.cuda.synchronize()
+    out = {}
+    for units in (256, 128):
+        with CuMaskedStream(first_units(units)) as ms:
+            def call():
+                fa.fa_fwd(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window,
+                          stream=ms.handle)
+            for _ in range(3):
+                call()
+            ms.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                call()
+            ms.synchronize()
+            out[str(units)] = round((time.perf_counter() - t0) * 1e3 / reps, 4)
+    return out
+
+
 def measured_ceilings():
     """What this machine sustains with nothing but matrix-core instructions (zero and random
     operands) and with a plain copy: the program built from csrc/ceilings.hip, run as a child
@@ -345,6 +430,8 @@ def main():
         out["config"]["layer_sequence"] = seqs
         conc_ms, batch_ms = three_sessions_time()
         out["config"]["three_sessions_16k"] = {"three_streams_ms": conc_ms, "one_batched_call_ms": batch_ms}
+        out["config"]["concurrent_requests_512"] = concurrent_requests_time()
+        out["config"]["co_location_8k_ms_by_compute_units"] = co_location_time()
 
     print(json.dumps(out))
 

@@ -107,3 +107,18 @@ def test_product_package_does_not_import_the_oracle():
         if path.suffix in (".py", ".cpp", ".hip", ".h"):
             text = path.read_text()
             assert "oracle" not in text.lower().replace("no cpu or pytorch fallback", ""), path
+
+
+def test_cu_mask_words():
+    """Mask words for a stream limited to the first compute units (host arithmetic only)."""
+    from paper_2603_12646_amd.cu_mask import first_units
+    import pytest as _pytest
+
+    assert first_units(256) == [0xFFFFFFFF] * 8
+    assert first_units(128) == [0xFFFFFFFF] * 4 + [0] * 4
+    assert first_units(40) == [0xFFFFFFFF, 0xFF, 0, 0, 0, 0, 0, 0]
+    assert first_units(1, 32) == [1]
+    assert sum(bin(w).count("1") for w in first_units(97)) == 97
+    for bad in (0, 257):
+        with _pytest.raises(ValueError):
+            first_units(bad)

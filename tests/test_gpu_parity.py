@@ -341,6 +341,98 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
                       label=f"graph replay {rep}")
 
 
+def test_concurrent_callers_on_their_own_streams():
+    """The paper's deployment runs several classifier sessions and many requests side by side
+    (Sec. 4.1.1, Sec. 5 concurrency table): eight host threads, each with its own stream, shape,
+    mask form and data, call the library at the same time, twenty times each.  The library
+    keeps no state between calls, so every thread's last output must match the oracle and
+    its first output bit for bit."""
+    import threading
+
+    cases = [  # (seed, B, H, N, lens, dtype, window)
+        (1200, 1, 12, 512, [512], "fp16", -1),
+        (1201, 1, 12, 512, [470], "bf16", 128),
+        (1202, 2, 4, 300, [300, 77], "fp16", -1),
+        (1203, 1, 3, 1000, [901], "bf16", -1),
+        (1204, 3, 2, 260, [260, 1, 130], "fp16", 64),
+        (1205, 1, 12, 512, [333], "fp16", 128),
+        (1206, 1, 2, 2048, [2048], "bf16", -1),
+        (1207, 2, 2, 640, [640, 639], "fp16", 256),
+    ]
+    work = []
+    for seed, B, H, N, lens, dtype, window in cases:
+        _, q, k, v = draw(seed, B, H, N, 64, dtype)
+        work.append(dict(q=to_dev(q, dtype), k=to_dev(k, dtype), v=to_dev(v, dtype), o=poison((B, H, N, 64), dtype),
+                         lse=torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda"),
+                         sl=torch.tensor(lens, dtype=torch.int32).cuda(), stream=torch.cuda.Stream(),
+                         host=(q, k, v), first=None, error=None))
+    torch.cuda.synchronize()
+    gate = threading.Barrier(len(cases))
+
+    def caller(i):
+        seed, B, H, N, lens, dtype, window = cases[i]
+        w = work[i]
+        fn = fa.fa_fwd if dtype == "fp16" else fa.fa_fwd_bf16
+        try:
+            gate.wait(timeout=60)
+            for rep in range(20):
+                fn(w["q"], w["k"], w["v"], w["o"], w["lse"], B, H, w["sl"], N, 64, 0.125, window, stream=w["stream"])
+                if rep == 0:
+                    w["stream"].synchronize()
+                    w["first"] = (w["o"].clone(), w["lse"].clone())
+                    with torch.cuda.stream(w["stream"]):
+                        w["o"].fill_(float("nan"))
+            w["stream"].synchronize()
+        except Exception as e:  # reported by the main thread
+            w["error"] = e
+
+    threads = [threading.Thread(target=caller, args=(i,)) for i in range(len(cases))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+        assert not t.is_alive()
+    torch.cuda.synchronize()
+    for i, (seed, B, H, N, lens, dtype, window) in enumerate(cases):
+        w = work[i]
+        assert w["error"] is None, f"caller {i}: {w['error']}"
+        assert torch.equal(w["first"][0], w["o"]) and torch.equal(w["first"][1], w["lse"]), f"caller {i}: calls differ"
+        L, R = window_from_width(window)
+        o_ref, lse_ref = attention_oracle(*w["host"], lens, 0.125, L, R)
+        check_against(w["o"].double().cpu().numpy(), w["lse"].double().cpu().numpy(), o_ref, lse_ref, lens, dtype,
+                      label=f"concurrent caller {i}")
+
+
+def test_call_on_a_stream_limited_to_half_the_compute_units():
+    """Co-location with another tenant (paper Sec. 1, Sec. 4.1.1): the caller hands over a stream
+    that may only use 128 of the 256 compute units.  Nothing in the kernels depends on how
+    many units run them, so global and local layers must give the same bits as on the
+    default stream, and match the oracle."""
+    from paper_2603_12646_amd.cu_mask import CuMaskedStream, first_units
+
+    B, H, N = 2, 6, 1500
+    lens = [1500, 1111]
+    _, q, k, v = draw(1300, B, H, N, 64, "bf16")
+    qd, kd, vd = (to_dev(x, "bf16") for x in (q, k, v))
+    sl = torch.tensor(lens, dtype=torch.int32).cuda()
+    torch.cuda.synchronize()
+    with CuMaskedStream(first_units(128)) as ms:
+        for window in (-1, 128):
+            o_m, o_d = poison((B, H, N, 64), "bf16"), poison((B, H, N, 64), "bf16")
+            lse_m = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+            lse_d = lse_m.clone()
+            torch.cuda.synchronize()
+            fa.fa_fwd_bf16(qd, kd, vd, o_m, lse_m, B, H, sl, N, 64, 0.125, window, stream=ms.handle)
+            ms.synchronize()
+            fa.fa_fwd_bf16(qd, kd, vd, o_d, lse_d, B, H, sl, N, 64, 0.125, window)
+            torch.cuda.synchronize()
+            assert torch.equal(o_m, o_d) and torch.equal(lse_m, lse_d)
+            L, R = window_from_width(window)
+            o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
+            check_against(o_m.double().cpu().numpy(), lse_m.double().cpu().numpy(), o_ref, lse_ref, lens, "bf16",
+                          label=f"half the compute units, window {window}")
+
+
 # ------------------------------------------------------------------ additive key bias
 def _random_bias(seed, B, N, dtype, holes=True, gain=2.0):
     rng = np.random.default_rng(seed)
