@@ -152,6 +152,10 @@ typedef struct fa_params {
 #define FA_TUNE_BM_AUTO 0x0u
 #define FA_TUNE_BM_128 0x1u  /* 4 wavefronts x 32 query rows  */
 #define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows (head_dim 64 only; ignored otherwise) */
+#define FA_TUNE_BM_32 0x3u   /* 32 query rows, the 4 wavefronts split the keys (global layers of
+                                head_dim 64 without a key bias; ignored otherwise).  The library
+                                picks it by itself when the call has at most 256 blocks of 32 query
+                                rows (one per compute unit) and max_len > 128. */
 #define FA_TUNE_V_AUTO 0x00u
 #define FA_TUNE_V_LDS_TRANSPOSE 0x10u /* ds_read_b64_tr_b16 operand loads */
 #define FA_TUNE_V_SCALAR 0x20u        /* 16-bit LDS reads (slow reference path) */

@@ -69,7 +69,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
     return FA_ERR_BAD_SHAPE;
   if (p->tuning & ~0x333u) return FA_ERR_BAD_TUNING;
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
-  if (t_bm > FA_TUNE_BM_256 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
+  if (t_bm > FA_TUNE_BM_32 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
     return FA_ERR_BAD_TUNING;
 
   FaKernelArgs a;
@@ -84,8 +84,22 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   // ... and so does a key bias unless it can ride on the pipelined global kernel
   const bool windowed = p->window_left >= 0 || p->window_right >= 0;
   const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
-  const int bm = (p->head_dim != 64 || bias_on_masked_kernel) ? 128
+  int bm = (p->head_dim != 64 || bias_on_masked_kernel) ? 128
                                    : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
+  // Key-split kernel (32 query rows per workgroup, the wavefronts split the keys): global
+  // layers of head_dim 64 without a bias whose 32-row blocks number at most one per compute
+  // unit (its workgroups use a whole unit's LDS, so a second round would cost more than the
+  // split gains).  Measured on MI355X against 128-row tiles: 1 x 12 heads x 512 and 1 x 4 x 512
+  // 7-15 % faster, 1 x 1 x 8192 38 % faster; 2 x 12 x 512 (two rounds) 32 % slower, 128 tokens
+  // no difference.  Its lanes address rows by 32-bit byte offsets from the (batch, head) slice.
+  {
+    const int64_t row_stride = a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2];
+    const bool eligible = p->head_dim == 64 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR &&
+                          (double)p->max_len * (double)row_stride * 2.0 < 4.0e9;
+    const int64_t blocks32 = (((int64_t)p->max_len + 31) / 32) * p->batch * p->heads;
+    if (eligible && (t_bm == FA_TUNE_BM_32 || (t_bm == FA_TUNE_BM_AUTO && blocks32 <= 256 && p->max_len > 128)))
+      bm = 32;
+  }
   const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
   const int64_t total = n_qtiles * p->batch * p->heads;
   // element count and grid must stay inside what the kernels index with

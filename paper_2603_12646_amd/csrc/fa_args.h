@@ -27,7 +27,7 @@ struct FaKernelArgs {
 };
 
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
-// bm: 128 or 256 query rows per workgroup; v_path: 0 = LDS transpose reads,
+// bm: 32 (key-split kernel), 128 or 256 query rows per workgroup; v_path: 0 = LDS transpose reads,
 // 1 = 16-bit reads.
 int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, void* stream);
 int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, void* stream);

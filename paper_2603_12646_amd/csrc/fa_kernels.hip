@@ -43,6 +43,10 @@
 //       LDS (the paper's 63/64 window): everything is requested at once, then each
 //       wavefront runs the same pipeline over the blocks its queries can see.
 //   fa_fwd_window_kernel  wider or one-sided windows: ring of 32-key stages.
+//   fa_fwd_keysplit_kernel  global layers of head_dim 64 with so few query tiles that the
+//       other kernels would leave most of the chip idle (one 512-token sequence): a
+//       workgroup owns 32 query rows, its four wavefronts split the KEYS, and the four
+//       partial results are merged through LDS.
 //   fa_fwd_masked_kernel  general path (register staging, padded tiles, optional 16-bit V
 //       reads) for head_dim 32, 64, 128: the production path of head_dim 32 and of the local
 //       layers of head_dim 128, and at head_dim 64 an independent implementation for the tests.
@@ -443,7 +447,9 @@ struct TileCoord {
   int b, h, qt, n, q0;
 };
 
-template <int BM>
+// CLAMP = false leaves tc.n as loaded (the caller clamps it into [0, max_len] when it first
+// needs it, so that the wait for the load can come after other work).
+template <int BM, bool CLAMP = true>
 __device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc) {
   if (a.map_xcd) {
     // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Tiles of
@@ -468,7 +474,7 @@ __device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc
   int n = a.max_len;
   if (a.seq_lens) {
     n = a.seq_lens[tc.b];
-    n = n < 0 ? 0 : (n > a.max_len ? a.max_len : n);
+    if (CLAMP) n = n < 0 ? 0 : (n > a.max_len ? a.max_len : n);
   }
   tc.n = n;
   tc.q0 = tc.qt * BM;
@@ -566,6 +572,73 @@ __device__ __forceinline__ void epilogue(const FaKernelArgs& a, RowState<NQB, D>
     if (lsep && hh == 0 && ig < N)
       lsep[ig] = live ? (st.mc[qb] + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
   }
+}
+
+// One unit of the resident pipelines (head_dim 64, one query block per wavefront, K/V
+// blocks as swizzled 32 x 64 tiles in LDS): probabilities of the current block from s_cur;
+// meanwhile the matrix cores form the NEXT block's scores (s_nxt, from k_next, started from
+// init(s_nxt): zero or a bias) and add the PREVIOUS block's P.V (p_prev, v_prev).
+// kb0: first key of the current block; interior: every valid query of the wavefront sees all
+// 32 keys, so no mask work; otherwise [jlo, jhi] is the lane's visible key range.
+// alive: the lane's query row exists.
+// EDGE = false is the straight-line form for the common unit - interior block, every existing
+// row already has a reference - whose only branch is the rare overflow redo at the end, so
+// that the compiler can interleave the vector work with the matrix products of the same
+// wavefront (with the mask and adoption branches in between it cannot); the caller checks
+// both conditions.  EDGE = true handles everything.
+template <class T, bool EDGE, class Init>
+__device__ __forceinline__ void resident_unit(RowState<1>& st, const typename T::v8 (&qreg)[1][4], floatx16& s_cur,
+                                              floatx16& s_nxt, typename T::v8 (&p_prev)[2],
+                                              typename T::v8 (&p_cur)[2], const uint16_t* k_next,
+                                              const uint16_t* v_prev, Init init, int kb0, bool interior, int jlo,
+                                              int jhi, bool alive, float c, int lane) {
+  const int l32 = lane & 31, hh = lane >> 5;
+  typename T::v8 ka[4], va[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag_swz<T>(k_next, l32, hh, ks);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) va[i] = load_vt_frag_swz<T>(v_prev, lane, i >> 1, i & 1);
+  init(s_nxt);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    s_nxt = T::mfma(ka[ks], qreg[0][ks], s_nxt);
+    st.oacc[0][ks & 1] = T::mfma(va[ks], p_prev[ks >> 1], st.oacc[0][ks & 1]);
+  }
+  uint32_t pk[8];
+  float blk;
+  uint32_t vis = 0xFFFFu;
+  if (EDGE && !interior) vis = visible_bits(kb0, hh, jlo, jhi);
+  // Rows that have not seen a key yet (the wavefront's first block, and the odd row whose
+  // window starts a block later) adopt this block's maximum as their reference.  Nothing
+  // has been accumulated for such a row, so there is nothing to rescale.
+  if (EDGE && __any(alive && st.m_ref[0] == -INFINITY)) {
+    float t0 = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+    const float tmax = max_xor32(t0);
+    if (st.m_ref[0] == -INFINITY) {
+      st.m_ref[0] = tmax;
+      st.mc[0] = tmax == -INFINITY ? 0.f : tmax * c;
+    }
+  }
+  if (!EDGE || interior) prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
+  else prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+  // !(blk <= limit) also catches a NaN sum
+  const bool trig = alive && !(blk <= kPLimit);
+  if (__any(trig)) {
+    // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
+    const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
+    float t0 = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+    const float tmax = max_xor32(t0);
+    rescale_rows(st, 0, row_trig, tmax, c);
+    if (EDGE) prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
+    else prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
+  }
+  st.lsum[0] += blk;
+  p_cur[0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+  p_cur[1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
 }
 
 // ======================================================================================
@@ -968,56 +1041,14 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
     auto unit = [&](floatx16& s_cur, floatx16& s_nxt, typename T::v8 (&p_prev)[2], typename T::v8 (&p_cur)[2], int u) {
       const int un = u + 1 > b_hi - 1 ? b_hi - 1 : u + 1;
       const int up = u - 1 < b_lo ? b_lo : u - 1;
-      const uint16_t* kblk = &lds_k[(un - b_lo) * kBlk];
-      const uint16_t* vblk = &lds_v[(up - b_lo) * kBlk];
-      typename T::v8 ka[4], va[4];
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) ka[ks] = load_k_frag_swz<T>(kblk, l32, hh, ks);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) va[i] = load_vt_frag_swz<T>(vblk, lane, i >> 1, i & 1);
-      score_init(s_nxt, un - b_lo);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        s_nxt = T::mfma(ka[ks], qreg[0][ks], s_nxt);
-        st.oacc[0][ks & 1] = T::mfma(va[ks], p_prev[ks >> 1], st.oacc[0][ks & 1]);
-      }
       // blocks every valid query of the wavefront sees completely need no mask work
       const int kb0 = u * 32;
       const bool interior = kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr;
-      uint32_t pk[8];
-      float blk;
-      uint32_t vis = 0xFFFFu;
-      if (!interior) vis = visible_bits(kb0, hh, jlo, jhi);
-      // Rows that have not seen a key yet (the wavefront's first block, and the odd row whose
-      // window starts a block later) adopt this block's maximum as their reference.  Nothing
-      // has been accumulated for such a row, so there is nothing to rescale.
-      if (__any(alive && st.m_ref[0] == -INFINITY)) {
-        float t0 = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
-        const float tmax = max_xor32(t0);
-        if (st.m_ref[0] == -INFINITY) {
-          st.m_ref[0] = tmax;
-          st.mc[0] = tmax == -INFINITY ? 0.f : tmax * c;
-        }
-      }
-      if (interior) prob_block<T, false>(s_cur, c, st.mc[0], vis, pk, blk);
-      else prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
-      // !(blk <= limit) also catches a NaN sum
-      const bool trig = alive && !(blk <= kPLimit);
-      if (__any(trig)) {
-        // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
-        const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
-        float t0 = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
-        const float tmax = max_xor32(t0);
-        rescale_rows(st, 0, row_trig, tmax, c);
-        prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
-      }
-      st.lsum[0] += blk;
-      p_cur[0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
-      p_cur[1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
+      // (the straight-line form of the unit measured no faster here: two wavefronts per SIMD
+      // already overlap each other's matrix and vector work)
+      resident_unit<T, true>(st, qreg, s_cur, s_nxt, p_prev, p_cur, &lds_k[(un - b_lo) * kBlk],
+                             &lds_v[(up - b_lo) * kBlk], [&](floatx16& sv) { score_init(sv, un - b_lo); }, kb0,
+                             interior, jlo, jhi, alive, c, lane);
     };
     auto drain = [&](typename T::v8 (&p_last)[2], int u) {
       const uint16_t* vblk = &lds_v[(u - b_lo) * kBlk];
@@ -1039,6 +1070,227 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   }
   __syncthreads();  // all blocks consumed: the K storage becomes the epilogue patches
   epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds_k + wave * kEpiPatch);
+}
+
+// ======================================================================================
+// Key-split kernel: global layers with very few query tiles (a single short sequence).
+// With 128-row tiles one 512-token sequence of 12 heads is 48 workgroups on 256 compute
+// units, one wavefront per SIMD walking 16 key blocks one after the other.  Here a
+// workgroup owns ONE 32-row query block and its four wavefronts split the keys: wavefront w
+// takes the 32-key blocks w, w+4, w+8, ...  Nothing is shared between wavefronts until the
+// end, so each stages its own blocks in a private ring of kSplitRing LDS slots (direct
+// global->LDS loads, no barriers; up to 512 keys everything is requested at once).  The
+// four partial (reference, sum, accumulator) states are then merged through LDS with the
+// split/merge identity of the online softmax, and wavefront 0 runs the common epilogue.
+// ======================================================================================
+constexpr int kSplitRing = 4;
+
+template <class T>
+__global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKernelArgs a) {
+  constexpr int BM = 32;
+  constexpr int kBlk = 32 * kD;  // elements per 32-key block
+  constexpr int kMergeVals = 35; // 32 accumulator values, reference, reference * c, sum share
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kWaves * kSplitRing * kBlk];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWaves * kSplitRing * kBlk];
+  __shared__ float mbuf[(kWaves - 1) * kMergeVals * 64];  // [wavefront 1..3][value][lane]
+  static_assert(kSplitRing * kBlk >= kEpiPatch, "wavefront 0's V ring doubles as its epilogue patch");
+
+  TileCoord tc;
+  if (!locate_tile<BM, false>(a, tc)) return;  // tc.n still as loaded: see below
+  const int N = a.max_len, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  uint16_t* my_k = &lds_k[wave * kSplitRing * kBlk];
+  uint16_t* my_v = &lds_v[wave * kSplitRing * kBlk];
+
+  // Block i of this wavefront is key block wave + 4 i and lives in ring slot i % kSplitRing.
+  // A block is 4 + 4 loads of 8 rows each (1 KB per load).  A lane's row is clamped to the
+  // last row of the tensor (rows >= n are masked or zeroed below), so its global offset is a
+  // per-lane 32-bit byte offset from the (batch, head) slice.
+  const int r8 = lane >> 3;
+  const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
+  auto issue_block = [&](int i) {
+    const int j = wave + kWaves * i, slot = i % kSplitRing;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int r = 8 * g + r8;  // row within the block
+      const int jg = 32 * j + r;
+      const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+      load16_to_lds(kp, jc * krow_b + 2u * (uint32_t)(((lane & 7) ^ k_swz(r)) * 8), &my_k[slot * kBlk + 8 * g * kD]);
+      load16_to_lds(vp, jc * vrow_b + 2u * (uint32_t)(((lane & 7) ^ v_swz(r)) * 8), &my_v[slot * kBlk + 8 * g * kD]);
+    }
+  };
+  // The first ring of blocks is requested from the tensor length alone, BEFORE the sequence
+  // length is looked at: reading it (device memory) then overlaps the loads instead of
+  // preceding them.  Blocks past the sequence end are fetched and never read.
+  const int nb_max = (N + 31) >> 5;
+  const int cnt_max = nb_max > wave ? (nb_max - wave + kWaves - 1) / kWaves : 0;
+  int issued = cnt_max < kSplitRing ? cnt_max : kSplitRing;  // blocks 0 .. issued-1 are requested
+#pragma unroll
+  for (int i = 0; i < kSplitRing; ++i)
+    if (i < issued) issue_block(i);
+
+  typename T::v8 qreg[1][4];
+  load_q<T, 1>(a, qp, q0, lane, qreg);  // every wavefront holds the same 32 query rows
+
+  // only now the sequence length
+  const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
+  tc.n = n;
+  if (q0 >= n) {
+    wait_direct_loads();  // the loads write this workgroup's LDS: they must land before it ends
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+  const int nb = (n + 31) >> 5;
+  const int cnt = nb > wave ? (nb - wave + kWaves - 1) / kWaves : 0;  // this wavefront's blocks; <= cnt_max
+
+  RowState<1> st;
+  init_state(st);
+  const bool alive = q0 + l32 < n;
+
+  // loads complete in order, 8 per block: block i has landed once at most 8 * (blocks
+  // requested after it) loads are outstanding
+  auto wait_for = [&](int i) {
+    const int younger = issued - 1 - i;
+    if (younger >= 3) __builtin_amdgcn_s_waitcnt(0x0F70 | 24);
+    else if (younger == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 16);
+    else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+  // V rows at or beyond n are overwritten with zeros by the lanes that fetched them (0 *
+  // whatever is stored in the padding must be 0); the slot is this wavefront's own
+  auto scrub = [&](int i) {
+    const int kb0 = 32 * (wave + kWaves * i);
+    if (kb0 + 32 <= n) return;
+    uint16_t* vblk = &my_v[(i % kSplitRing) * kBlk];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      if (kb0 + 8 * g + r8 >= n) *(uint4*)&vblk[(8 * g + r8) * kD + (lane & 7) * 8] = make_uint4(0, 0, 0, 0);
+  };
+
+  if (cnt > 0) {
+    // the same software pipeline as the resident window kernel, over this wavefront's blocks
+    floatx16 sA, sB;
+    typename T::v8 pA[2], pB[2];
+    pA[0] = pA[1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+    auto zero_scores = [](floatx16& sv) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sv[r] = 0.f;
+    };
+    wait_for(0);
+    scrub(0);
+    zero_scores(sA);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) sA = T::mfma(load_k_frag_swz<T>(my_k, l32, hh, ks), qreg[0][ks], sA);
+    // A global layer shows every existing row at least one key of the wavefront's first block:
+    // the rows take its maximum as their reference here, once, so that every full block can
+    // run the straight-line unit (nothing is accumulated yet, so there is nothing to rescale).
+    {
+      const int kb0 = 32 * wave;
+      const uint32_t vis = kb0 + 32 <= n ? 0xFFFFu : visible_bits(kb0, hh, 0, n - 1);
+      float t0 = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? sA[r] : -INFINITY);
+      const float tmax = max_xor32(t0);
+      st.m_ref[0] = tmax;
+      st.mc[0] = tmax == -INFINITY ? 0.f : tmax * a.c;
+    }
+
+    // Unit i: probabilities of block i; scores of block i+1; P.V of block i-1.  At the two
+    // ends the neighbour is clamped: its product is unused (scores) or multiplied by zero
+    // probabilities (P.V).
+    auto unit = [&](floatx16& s_cur, floatx16& s_nxt, typename T::v8 (&p_prev)[2], typename T::v8 (&p_cur)[2], int i) {
+      const int in = i + 1 < cnt ? i + 1 : cnt - 1;
+      const int ip = i > 0 ? i - 1 : 0;
+      if (i + 1 < cnt) {
+        wait_for(i + 1);
+        scrub(i + 1);
+      }
+      const int kb0 = 32 * (wave + kWaves * i);
+      if (kb0 + 32 <= n)
+        resident_unit<T, false>(st, qreg, s_cur, s_nxt, p_prev, p_cur, &my_k[(in % kSplitRing) * kBlk],
+                                &my_v[(ip % kSplitRing) * kBlk], zero_scores, kb0, true, 0, n - 1, alive, a.c, lane);
+      else
+        resident_unit<T, true>(st, qreg, s_cur, s_nxt, p_prev, p_cur, &my_k[(in % kSplitRing) * kBlk],
+                               &my_v[(ip % kSplitRing) * kBlk], zero_scores, kb0, kb0 + 32 <= n, 0, n - 1, alive, a.c,
+                               lane);
+      // block i-1 is consumed (its fragments are in registers): refill its slot.  Only
+      // sequences beyond kSplitRing blocks per wavefront (512 keys) get here.
+      if (i >= 1 && i - 1 + kSplitRing < cnt) {
+        issue_block(i - 1 + kSplitRing);
+        issued = i + kSplitRing;
+      }
+    };
+    auto drain = [&](typename T::v8 (&p_last)[2], int i) {
+      const uint16_t* vblk = &my_v[(i % kSplitRing) * kBlk];
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+        st.oacc[0][x & 1] = T::mfma(load_vt_frag_swz<T>(vblk, lane, x >> 1, x & 1), p_last[x >> 1], st.oacc[0][x & 1]);
+    };
+    int i = 0;
+    for (; i + 1 < cnt; i += 2) {
+      unit(sA, sB, pA, pB, i);
+      unit(sB, sA, pB, pA, i + 1);
+    }
+    if (i < cnt) {
+      unit(sA, sB, pA, pB, i);
+      drain(pB, i);
+    } else {
+      drain(pA, cnt - 1);
+    }
+  }
+  // blocks requested beyond this wavefront's share of [0, n) may still be landing in its ring
+  wait_direct_loads();
+
+  // ---- merge the four partial results (same lane <-> (row, column) mapping in every wavefront)
+  if (wave > 0) {
+    float* dst = mbuf + (wave - 1) * kMergeVals * 64 + lane;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dst[(16 * db + r) * 64] = st.oacc[0][db][r];
+    dst[32 * 64] = st.m_ref[0];
+    dst[33 * 64] = st.mc[0];
+    dst[34 * 64] = st.lsum[0];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  {
+    float m_new = st.m_ref[0];
+#pragma unroll
+    for (int w = 0; w < kWaves - 1; ++w) m_new = fmaxf(m_new, mbuf[w * kMergeVals * 64 + 32 * 64 + lane]);
+    const float mc_new = (m_new == -INFINITY) ? 0.f : m_new * a.c;
+    // a wavefront that saw no key has nothing accumulated: factor 0, kept away from exp2(+inf)
+    const float f0 = (st.m_ref[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.mc[0] - mc_new);
+    st.lsum[0] *= f0;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.oacc[0][db][r] *= f0;
+#pragma unroll
+    for (int w = 0; w < kWaves - 1; ++w) {
+      const float* src = mbuf + w * kMergeVals * 64 + lane;
+      const float f = (src[32 * 64] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(src[33 * 64] - mc_new);
+      st.lsum[0] = __builtin_fmaf(f, src[34 * 64], st.lsum[0]);
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          st.oacc[0][db][r] = __builtin_fmaf(f, src[(16 * db + r) * 64], st.oacc[0][db][r]);
+    }
+    st.m_ref[0] = m_new;
+    st.mc[0] = mc_new;
+  }
+  epilogue<T, 1, kD>(a, st, op, lsep, q0, n, lane, lds_v);
 }
 
 // ======================================================================================
@@ -1425,6 +1677,9 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
       if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true>), dim3(grid), block, 0, s, a);
       else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, false>), dim3(grid), block, 0, s, a);
     }
+  } else if (bm == 32) {
+    // the host asks for 32-row tiles only for global layers of head_dim 64 without a bias
+    hipLaunchKernelGGL((fa_fwd_keysplit_kernel<T>), dim3(grid), block, 0, s, a);
   } else if (global && v_path == 0) {
     if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2>), dim3(grid), block, 0, s, a);
     else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2>), dim3(grid), block, 0, s, a);

@@ -23,14 +23,22 @@ def poison(shape, dtype):
     return torch.full(shape, float("nan"), dtype=TORCH_DT[dtype], device="cuda")
 
 
-def run_simple(q32, k32, v32, lens, dtype, scale, window=-1, want_lse=True, stream=None):
+def run_simple(q32, k32, v32, lens, dtype, scale, window=-1, want_lse=True, stream=None, tuning=0):
+    """The plain entry points; with a nonzero `tuning` the same call goes through fa_fwd_ex
+    (window width mapped to left/right as the plain entry points do) so that a kernel shape
+    can be forced."""
     B, H, N, D = q32.shape
     q, k, v = to_dev(q32, dtype), to_dev(k32, dtype), to_dev(v32, dtype)
     o = poison((B, H, N, D), dtype)
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     sl = None if lens is None else torch.as_tensor(np.asarray(lens), dtype=torch.int32).cuda()
-    fn = fa.fa_fwd if dtype == "fp16" else fa.fa_fwd_bf16
-    fn(q, k, v, o, lse, B, H, sl, N, D, scale, window, stream=stream)
+    if tuning:
+        left, right = (-1, -1) if window < 0 else ((window - 1) // 2, window // 2)
+        fa.fa_fwd_ex(dtype=FA_DT[dtype], q=q, k=k, v=v, o=o, lse=lse, seq_lens=sl, batch=B, heads=H, max_len=N,
+                     head_dim=D, scale=scale, window_left=left, window_right=right, tuning=tuning, stream=stream)
+    else:
+        fn = fa.fa_fwd if dtype == "fp16" else fa.fa_fwd_bf16
+        fn(q, k, v, o, lse, B, H, sl, N, D, scale, window, stream=stream)
     torch.cuda.synchronize()
     return o.double().cpu().numpy(), (None if lse is None else lse.double().cpu().numpy())
 

@@ -83,7 +83,7 @@ def test_ex_entry_point_rejects_bad_arguments():
                 stream=0, check=False)
     assert fa.fa_fwd_ex(**{**base, "dtype": 7}) == -7
     assert fa.fa_fwd_ex(**{**base, "tuning": 0x4000}) == -9
-    assert fa.fa_fwd_ex(**{**base, "tuning": 0x3}) == -9
+    assert fa.fa_fwd_ex(**{**base, "tuning": 0x4}) == -9
     assert fa.fa_fwd_ex(**{**base, "q_strides": (512, 64, 65)}) == -6
     assert fa.fa_fwd_ex(**{**base, "k_strides": (512, 64, 32)}) == -2
     assert fa.fa_fwd_ex(**{**base, "key_bias": P + 1}) == -6

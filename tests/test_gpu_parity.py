@@ -24,7 +24,13 @@ TUNINGS = {
     "bm256_tr": fa.FA_TUNE_BM_256 | fa.FA_TUNE_V_LDS_TRANSPOSE | fa.FA_TUNE_MAP_LINEAR,
     "bm128_scalar_xcd": fa.FA_TUNE_BM_128 | fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_XCD,
     "bm256_scalar_xcd": fa.FA_TUNE_BM_256 | fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_XCD,
+    "bm32_linear": fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_LINEAR,
+    "bm32_xcd": fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_XCD,
 }
+# Small global calls take the key-split kernel by themselves (at most 256 blocks of 32 query
+# rows, more than 128 tokens); the small-shape tests below therefore run three times: the
+# library's choice, the pipelined kernel forced, the key-split kernel forced.
+GLOBAL_KERNELS = {"auto": 0, "bm128": fa.FA_TUNE_BM_128, "bm32": fa.FA_TUNE_BM_32}
 
 
 # ------------------------------------------------------------------ small shapes, full compare
@@ -42,68 +48,75 @@ def test_small_ragged_all_windows(dtype, left, right, tuning):
     check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"{dtype} {left},{right} {tuning}")
 
 
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 @pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 640])
-def test_lengths_around_tile_edges(dtype, N):
+def test_lengths_around_tile_edges(dtype, N, kern):
     B, H, D = 1, 2, 64
     _, q, k, v = draw(200 + N, B, H, N, D, dtype)
-    for window in (-1, 128, 2):
+    for window in ((-1, 128, 2) if kern == "auto" else (-1,)):
         L, R = window_from_width(window)
         o_ref, lse_ref = attention_oracle(q, k, v, None, 0.125, L, R)
-        o, lse = run_simple(q, k, v, None, dtype, 0.125, window)
-        check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"N={N} w={window}")
+        o, lse = run_simple(q, k, v, None, dtype, 0.125, window, tuning=GLOBAL_KERNELS[kern])
+        check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"N={N} w={window} {kern}")
 
 
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
-def test_seq_lens_degenerate_values(dtype):
+def test_seq_lens_degenerate_values(dtype, kern):
     """n_b = 0, negative, above max_len (clamped), 1, and exactly a tile edge."""
     B, H, N, D = 6, 2, 192, 64
     _, q, k, v = draw(300, B, H, N, D, dtype)
     lens = [0, -5, 1000, 1, 128, 191]
-    for window in (-1, 128):
+    for window in ((-1, 128) if kern == "auto" else (-1,)):
         L, R = window_from_width(window)
         o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
-        o, lse = run_simple(q, k, v, lens, dtype, 0.125, window)
-        check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"w={window}")
+        o, lse = run_simple(q, k, v, lens, dtype, 0.125, window, tuning=GLOBAL_KERNELS[kern])
+        check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"w={window} {kern}")
 
 
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
-def test_padded_rows_may_hold_anything(dtype):
+def test_padded_rows_may_hold_anything(dtype, kern):
     """NaN / inf / huge values in padded Q, K, V rows leave valid rows bit-identical."""
     B, H, N, D = 2, 2, 300, 64
     _, q, k, v = draw(301, B, H, N, D, dtype)
     lens = [170, 255]
-    for window in (-1, 128):
-        a_o, a_lse = run_simple(q, k, v, lens, dtype, 0.125, window)
+    tun = GLOBAL_KERNELS[kern]
+    for window in ((-1, 128) if kern == "auto" else (-1,)):
+        a_o, a_lse = run_simple(q, k, v, lens, dtype, 0.125, window, tuning=tun)
         q2, k2, v2 = q.copy(), k.copy(), v.copy()
         for b, n in enumerate(lens):
             q2[b, :, n:] = np.inf
             k2[b, :, n:] = np.nan
             v2[b, :, n:] = np.nan
             v2[b, :, n::2] = -np.inf
-        b_o, b_lse = run_simple(q2, k2, v2, lens, dtype, 0.125, window)
+        b_o, b_lse = run_simple(q2, k2, v2, lens, dtype, 0.125, window, tuning=tun)
         assert np.array_equal(a_o, b_o) and np.array_equal(a_lse, b_lse)
         L, R = window_from_width(window)
         o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
         check_against(b_o, b_lse, o_ref, lse_ref, lens, dtype, label=f"poisoned w={window}")
 
 
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 @pytest.mark.parametrize("scale", [0.0, -0.125, 1.0, 0.3, 8.0])
-def test_scales(dtype, scale):
+def test_scales(dtype, scale, kern):
     """scale = 0 (uniform attention), negative, not a power of two, and large
     (near one-hot softmax, running maximum far from zero)."""
     B, H, N, D = 1, 2, 200, 64
     _, q, k, v = draw(302, B, H, N, D, dtype)
     lens = [187]
     o_ref, lse_ref = attention_oracle(q, k, v, lens, scale)
-    o, lse = run_simple(q, k, v, lens, dtype, scale)
-    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"scale={scale}")
+    o, lse = run_simple(q, k, v, lens, dtype, scale, tuning=GLOBAL_KERNELS[kern])
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"scale={scale} {kern}")
 
 
-def test_increasing_scores_force_many_rescales():
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
+def test_increasing_scores_force_many_rescales(kern):
     """Keys ordered so every tile's maximum beats the previous one by a wide margin:
     the reference maximum must be refreshed tile after tile."""
+    tun = GLOBAL_KERNELS[kern]
     N, D = 512, 64
     rng = np.random.default_rng(7)
     q = np.zeros((1, 1, N, D), np.float32); q[..., 0] = 1.0
@@ -113,16 +126,16 @@ def test_increasing_scores_force_many_rescales():
     for dtype in ("fp16", "bf16"):
         k, v = round_to_storage(k0, dtype), round_to_storage(v0, dtype)
         o_ref, lse_ref = attention_oracle(q, k, v, None, 1.0)
-        o, lse = run_simple(q, k, v, None, dtype, 1.0)
+        o, lse = run_simple(q, k, v, None, dtype, 1.0, tuning=tun)
         check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp")
         o_ref, lse_ref = attention_oracle(q, k[:, :, ::-1].copy(), v, None, 1.0)
-        o, lse = run_simple(q, k[:, :, ::-1].copy(), v, None, dtype, 1.0)
+        o, lse = run_simple(q, k[:, :, ::-1].copy(), v, None, dtype, 1.0, tuning=tun)
         check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label="ramp down")
         # steeper ramps: a block's probabilities against the stale reference overflow the
         # storage type (scale 8) and even fp32 (scale 40) before the refresh catches them
         for scale in (8.0, 40.0):
             o_ref, lse_ref = attention_oracle(q, k, v, None, scale)
-            o, lse = run_simple(q, k, v, None, dtype, scale)
+            o, lse = run_simple(q, k, v, None, dtype, scale, tuning=tun)
             check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"steep ramp {scale}")
 
 
@@ -177,6 +190,69 @@ def test_strided_inputs_bshd_and_packed_qkv(dtype):
     torch.cuda.synchronize()
     o_np = o.double().cpu().numpy().transpose(0, 2, 1, 3)
     check_against(o_np, lse.double().cpu().numpy(), o_ref, lse_ref, lens, dtype, relative=True, label="strided")
+
+
+@pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
+def test_strided_inputs_global_layer(kern):
+    """Packed QKV read in place by both global-layer kernels of head_dim 64."""
+    B, H, N, D = 2, 3, 300, 64
+    _, q, k, v = draw(306, B, H, N, D, "fp16")
+    lens = [300, 211]
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125)
+    packed = np.stack([q, k, v], axis=0).transpose(1, 3, 0, 2, 4).copy()  # B, N, 3, H, D
+    dev = to_dev(packed, "fp16")
+    o = poison((B, N, H, D), "fp16")
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    sl = torch.tensor(lens, dtype=torch.int32).cuda()
+    st = (N * 3 * H * D, D, 3 * H * D)
+    fa.fa_fwd_ex(dtype=FA_DT["fp16"], q=dev[:, :, 0].data_ptr(), k=dev[:, :, 1].data_ptr(),
+                 v=dev[:, :, 2].data_ptr(), o=o, lse=lse, seq_lens=sl, batch=B, heads=H, max_len=N,
+                 scale=0.125, q_strides=st, k_strides=st, v_strides=st, o_strides=(N * H * D, D, H * D),
+                 tuning=GLOBAL_KERNELS[kern])
+    torch.cuda.synchronize()
+    o_np = o.double().cpu().numpy().transpose(0, 2, 1, 3)
+    check_against(o_np, lse.double().cpu().numpy(), o_ref, lse_ref, lens, "fp16", relative=True, label=f"strided {kern}")
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("B,H,N,lens", [
+    (1, 1, 2100, [2049]),       # 17 blocks per wavefront: the ring of four slots is refilled many times
+    (1, 2, 700, [40]),          # first ring requested from max_len, sequence far shorter: blocks fetched and dropped
+    (2, 1, 640, [97, 640]),     # wavefront 3 has one partial block / five full ones
+    (1, 3, 130, [65]),          # wavefront 3 (and 2 for most rows) has no block at all
+    (1, 1, 4128, [4128]),       # exactly 129 blocks
+    (3, 1, 513, [0, 513, 1]),   # empty sequence, one key
+])
+def test_key_split_kernel_ring_and_ragged_ends(dtype, B, H, N, lens):
+    """The key-split kernel forced on shapes that exercise its private ring, the early
+    request of blocks past the sequence end, wavefronts without work, and the merge of
+    partial results when some of them are empty; padded rows hold NaN."""
+    _, q, k, v = draw(1400 + N, B, H, N, 64, dtype)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125)
+    for b, n in enumerate(lens):
+        k[b, :, n:] = np.nan
+        v[b, :, n:] = np.nan
+    o, lse = run_simple(q, k, v, lens, dtype, 0.125, tuning=fa.FA_TUNE_BM_32)
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"key split {B}x{H}x{N}")
+    o2, lse2 = run_simple(q, k, v, lens, dtype, 0.125, tuning=fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_LINEAR)
+    assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+
+
+def test_key_split_merge_with_far_apart_maxima():
+    """Each wavefront's share of the keys has its own score level (key block j scores about
+    6 * (j % 4) higher): the merge has to scale three of the four partial results far down."""
+    N, D = 512, 64
+    rng = np.random.default_rng(11)
+    q = np.zeros((1, 1, N, D), np.float32); q[..., 0] = 1.0
+    k0 = rng.standard_normal((1, 1, N, D)).astype(np.float32) * 0.1
+    k0[0, 0, :, 0] = 6.0 * ((np.arange(N) // 32) % 4)
+    v0 = rng.standard_normal((1, 1, N, D)).astype(np.float32)
+    for dtype in ("fp16", "bf16"):
+        k, v = round_to_storage(k0, dtype), round_to_storage(v0, dtype)
+        for scale in (1.0, 4.0):
+            o_ref, lse_ref = attention_oracle(q, k, v, None, scale)
+            o, lse = run_simple(q, k, v, None, dtype, scale, tuning=fa.FA_TUNE_BM_32)
+            check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"merge {dtype} {scale}")
 
 
 @pytest.mark.parametrize("D,left,right", [(128, -1, -1), (128, 10, 20), (32, -1, -1)])

@@ -32,7 +32,7 @@ def draw_case(rng, case):
     else:
         left, right = -1, int(rng.integers(0, 100))
     scale = float(rng.choice([1.0 / np.sqrt(D), 0.3, -0.1, 0.02]))
-    tuning = int(rng.choice([0, 0, 0x1, 0x2, 0x20, 0x100, 0x201]))
+    tuning = int(rng.choice([0, 0, 0x1, 0x2, 0x3, 0x20, 0x100, 0x201, 0x103]))
     bias = None
     if rng.random() < 0.4:
         # bf16 gets a milder bias so that outputs stay below 1 in magnitude
