@@ -122,3 +122,53 @@ def test_cu_mask_words():
     for bad in (0, 257):
         with _pytest.raises(ValueError):
             first_units(bad)
+
+
+C_CALLER = r"""
+#include <stddef.h>
+#include <stdio.h>
+#include <string.h>
+#include "fa.h"
+
+int main(void) {
+  fa_params p;
+  memset(&p, 0, sizeof p);
+  p.struct_size = (uint32_t)sizeof p;
+  printf("%d %u %u %u %u %u %d %d %d %s\n", fa_version(), (unsigned)sizeof(fa_params),
+         (unsigned)offsetof(fa_params, q_strides), (unsigned)offsetof(fa_params, stream),
+         (unsigned)offsetof(fa_params, tuning), (unsigned)offsetof(fa_params, key_bias),
+         fa_fwd(NULL, NULL, NULL, NULL, NULL, 1, 1, NULL, 8, 64, 1.0f, -1, NULL),
+         fa_fwd_ex(&p), (int)fa_workspace_bytes(1, 12, 512, 64), fa_strerror(0));
+  return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_its_struct_layout_is_the_bindings(tmp_path):
+    """A C99 caller compiled with gcc -pedantic against include/fa.h and linked to the built
+    library: the header needs nothing but <stdint.h>/<stddef.h>, the error paths answer
+    without a device, and the struct the C compiler lays out is the one the Python binding
+    fills."""
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "caller.c"
+    src.write_text(C_CALLER)
+    exe = tmp_path / "caller"
+    libdir = str(pathlib.Path(fa.LIB_PATH).parent)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", str(ROOT / "include"),
+                    str(src), "-o", str(exe), fa.LIB_PATH, f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 9)
+    m = re.search(r"#define FA_VERSION (\d+)", HEADER)
+    assert int(out[0]) == int(m.group(1))
+    assert int(out[1]) == ctypes.sizeof(fa.FaParams)
+    assert int(out[2]) == fa.FaParams.q_strides.offset
+    assert int(out[3]) == fa.FaParams.stream.offset
+    assert int(out[4]) == fa.FaParams.tuning.offset
+    assert int(out[5]) == fa.FaParams.key_bias.offset
+    assert int(out[6]) < 0 and int(out[7]) < 0      # null pointers: rejected on the host
+    assert int(out[8]) == 0
+    assert out[9].strip() == fa.fa_strerror(0)
