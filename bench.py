@@ -138,7 +138,8 @@ def layer_sequence_time(w, lens, q, k, v, layers=22, every=3, window=128, reps=5
     """Attention calls of one pass through a ModernBERT-shaped encoder (paper Sec. 2.4 and
     4.1.3: local layers with a 128-token window, every third layer global): `layers` calls
     back to back on the workload's tensors, global when layer % every == 0.  Returns
-    (ms per pass, number of global layers)."""
+    (ms per pass launched call by call, ms per pass replayed from a HIP graph, number of
+    global layers)."""
     import torch
     import paper_2603_12646_amd as fa
 
@@ -163,7 +164,29 @@ def layer_sequence_time(w, lens, q, k, v, layers=22, every=3, window=128, reps=5
         one_pass()
     stop.record()
     torch.cuda.synchronize()
-    return start.elapsed_time(stop) / reps, n_global
+    eager_ms = start.elapsed_time(stop) / reps
+
+    # the same 22 launches recorded once into a HIP graph and replayed: no host work between
+    # the kernels (the library allocates nothing and never synchronises, so it can be captured)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_pass()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_pass()
+    graph.replay()
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        graph.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    graph_ms = start.elapsed_time(stop) / reps
+    del graph
+    return eager_ms, graph_ms, n_global
 
 
 def three_sessions_time(reps=10):
@@ -468,11 +491,12 @@ def main():
         out["config"]["other_workloads"] = others
         # one encoder pass worth of attention calls (22 layers, every third global) at 8K and 32K
         seqs = {}
-        for name in ("c3_8k", "c5a_32k_global"):
+        for name in ("c1_512", "c3_8k", "c5a_32k_global"):
             lw = ALL_CONFIGS[name]
             ll, lq, lk, lv = make_inputs(lw)
-            ms, n_global = layer_sequence_time(lw, ll, lq, lk, lv)
-            seqs[name] = {"layers": 22, "global_layers": n_global, "local_window": 128, "ms_per_pass": ms}
+            ms, graph_ms, n_global = layer_sequence_time(lw, ll, lq, lk, lv)
+            seqs[name] = {"layers": 22, "global_layers": n_global, "local_window": 128, "ms_per_pass": ms,
+                          "ms_per_pass_hip_graph": graph_ms}
             del lq, lk, lv
         out["config"]["layer_sequence"] = seqs
         conc_ms, batch_ms = three_sessions_time()
