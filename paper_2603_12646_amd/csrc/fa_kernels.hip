@@ -914,8 +914,8 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? kResBlocks * 32 : 4];
 
   TileCoord tc;
-  if (!locate_tile<BM>(a, tc)) return;
-  const int N = a.max_len, n = tc.n, q0 = tc.q0;
+  if (!locate_tile<BM, false>(a, tc)) return;  // tc.n still as loaded: see below
+  const int N = a.max_len, q0 = tc.q0;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -927,24 +927,24 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
   float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
 
-  if (q0 >= n) {
-    zero_fill<BM>(a, tc, op, lsep);
-    return;
-  }
-
-  // key range of this workgroup, in 32-key blocks; block b lives in slot b - b_lo
-  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  // Key blocks this tile can touch, from the tile position and the tensor length alone: the
+  // loads below are issued BEFORE the sequence length is looked at, so that the latency of
+  // reading it (it sits in device memory) overlaps theirs instead of preceding it - a
+  // workgroup that is alone on its compute unit (short sequences) has nothing else to hide
+  // it behind.  Block b lives in slot b - b_lo; blocks past the sequence end are fetched and
+  // never read.
   const int lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
-  const int hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
   const int b_lo = lo >> 5;
-  int b_hi = (hi + 31) >> 5;
-  if (b_hi > b_lo + kResBlocks) b_hi = b_lo + kResBlocks;  // never true for the windows the host routes here
+  int b_hi_ld = (q0 + BM + a.wr + 31) >> 5;
+  b_hi_ld = b_hi_ld < ((N + 31) >> 5) ? b_hi_ld : ((N + 31) >> 5);
+  if (b_hi_ld > b_lo + kResBlocks) b_hi_ld = b_lo + kResBlocks;  // never true for the windows the host routes here
 
   // Wavefront w moves rows 8w..8w+7 of every block (one 1 KB load each for K and V).  A
   // lane's row is clamped to the last row of the tensor (rows >= n are masked or zeroed
   // below), so its global offset is a per-lane 32-bit byte offset from the slice.
   const int dl_r = 8 * wave + (lane >> 3);
   {
+    const int b_hi = b_hi_ld;
     const uint32_t kchunk = 2u * (uint32_t)(((lane & 7) ^ k_swz(dl_r)) * 8);
     const uint32_t vchunk = 2u * (uint32_t)(((lane & 7) ^ v_swz(dl_r)) * 8);
     const uint32_t krow_b = 2u * (uint32_t)a.ks[2], vrow_b = 2u * (uint32_t)a.vs[2];
@@ -983,10 +983,23 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
   }
 
   const int qw0 = q0 + wave * 32;
-  const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
-  const bool wave_has_rows = qw_last >= qw0;
   typename T::v8 qreg[1][4];
   load_q<T, 1>(a, qp, qw0, lane, qreg);
+
+  // only now the sequence length
+  const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
+  tc.n = n;
+  if (q0 >= n) {
+    wait_direct_loads();  // the loads write this workgroup's LDS: they must land before it ends
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  const int hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
+  int b_hi = (hi + 31) >> 5;  // blocks [b_lo, b_hi) hold visible keys
+  if (b_hi > b_hi_ld) b_hi = b_hi_ld;
+  const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
+  const bool wave_has_rows = qw_last >= qw0;
   RowState<1> st;
   init_state(st);
   const int ig = qw0 + l32;
