@@ -60,7 +60,7 @@
 extern "C" {
 #endif
 
-#define FA_VERSION 200 /* major*10000 + minor*100 + patch */
+#define FA_VERSION 201 /* major*10000 + minor*100 + patch */
 
 enum {
   FA_OK = 0,
