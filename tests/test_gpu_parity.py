@@ -646,6 +646,27 @@ def test_named_large_configs_sampled_rows(name):
     assert worst <= tol["max_abs"] and total / count <= tol["mean_abs"]
 
 
+@pytest.mark.parametrize("dtype,window,tuning", [("bf16", -1, 0), ("fp16", 128, 0), ("fp16", -1, fa.FA_TUNE_BM_32),
+                                                 ("bf16", 700, 0)])
+def test_quarter_million_tokens_sampled_rows(dtype, window, tuning):
+    """Eight times the longest named workload: one head of 262 144 tokens (a key-padding tail
+    of 1 000), where row offsets pass 2^24 bytes and a row's sum runs over 261 144 keys.
+    Global (pipelined and key-split kernels), the 128-key window and a 700-key window (ring
+    kernel); sampled rows against the oracle, padded rows exhaustively."""
+    B, H, N, D = 1, 1, 262144, 64
+    n = N - 1000
+    _, q, k, v = draw(1500, B, H, N, D, dtype)
+    L, R = window_from_width(window)
+    o, lse = run_simple(q, k, v, [n], dtype, 0.125, window, tuning=tuning)
+    assert np.all(o[0, :, n:] == 0) and np.all(np.isneginf(lse[0, :, n:]))
+    rows = sample_rows(n, np.random.default_rng(12), 160)
+    o_ref, lse_ref = attention_oracle_rows(q, k, v, 0, 0, rows, n, 0.125, L, R)
+    d = np.abs(o[0, 0, rows] - o_ref)
+    assert np.all(np.isfinite(o[0, 0, rows]))
+    assert d.max() <= TOL[dtype]["max_abs"] and d.mean() <= TOL[dtype]["mean_abs"], (d.max(), d.mean())
+    assert np.abs(lse[0, 0, rows] - lse_ref).max() <= LSE_TOL
+
+
 # ------------------------------------------------------------------ measurement helper program
 def test_ceilings_program_reports_plausible_numbers():
     """The standalone program bench.py runs for its `ceilings` block: matrix-core rate with
