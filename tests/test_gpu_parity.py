@@ -667,6 +667,22 @@ def test_quarter_million_tokens_sampled_rows(dtype, window, tuning):
     assert np.abs(lse[0, 0, rows] - lse_ref).max() <= LSE_TOL
 
 
+@pytest.mark.parametrize("window", [-1, 16])
+def test_thousands_of_tiny_sequences(window):
+    """3 000 sequences of 0 to 40 tokens, 3 heads: the grid is almost all batch index, most
+    tiles are ragged or empty, and every XCD's share of a batch element is a fraction of a tile
+    row.  Full compare, both tile orders."""
+    B, H, N, D = 3000, 3, 40, 64
+    rng = np.random.default_rng(13)
+    lens = rng.integers(0, N + 1, size=B).tolist()
+    _, q, k, v = draw(1600, B, H, N, D, "fp16")
+    L, R = window_from_width(window)
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
+    for tuning in (fa.FA_TUNE_MAP_XCD, fa.FA_TUNE_MAP_LINEAR):
+        o, lse = run_ex(q, k, v, lens, "fp16", 0.125, L, R, tuning=tuning)
+        check_against(o, lse, o_ref, lse_ref, lens, "fp16", relative=True, label=f"tiny sequences {window} {tuning:#x}")
+
+
 # ------------------------------------------------------------------ measurement helper program
 def test_ceilings_program_reports_plausible_numbers():
     """The standalone program bench.py runs for its `ceilings` block: matrix-core rate with
