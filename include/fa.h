@@ -47,7 +47,8 @@
  *   0  success (work enqueued).
  *   <0 FA_ERR_*: an invalid argument, detected on the host before anything touches
  *      the device; nothing was enqueued.
- *   >0 the hipError_t reported by the launch.
+ *   >0 the hipError_t returned by this call's own kernel launch (an error left behind
+ *      by the caller's earlier HIP work is neither reported nor cleared).
  *   No exceptions, no aborts, nothing is printed.
  */
 #ifndef FA_H
@@ -65,10 +66,13 @@ extern "C" {
 enum {
   FA_OK = 0,
   FA_ERR_NULL_POINTER = -1,  /* q, k, v or o is NULL (or params is NULL)               */
-  FA_ERR_BAD_SHAPE = -2,     /* batch, heads or max_len <= 0, or too large for a grid  */
+  FA_ERR_BAD_SHAPE = -2,     /* batch, heads or max_len <= 0, or too large for a grid;
+                                a row stride below head_dim; o strides under which two
+                                output rows would overlap (zero, negative, interleaved) */
   FA_ERR_BAD_HEAD_DIM = -3,  /* head_dim not in the supported set {32, 64, 128}        */
   FA_ERR_BAD_SCALE = -4,     /* scale is NaN or infinite (0 and negatives are legal)   */
-  FA_ERR_BAD_WINDOW = -5,    /* window == 0 (fa_fwd); window_left/right inconsistent   */
+  FA_ERR_BAD_WINDOW = -5,    /* window == 0 (fa_fwd, fa_fwd_bf16 only: every pair of
+                                window_left / window_right is legal for fa_fwd_ex)     */
   FA_ERR_MISALIGNED = -6,    /* a tensor pointer is not 16-byte aligned, or a stride
                                 is not a multiple of 8 elements                        */
   FA_ERR_BAD_DTYPE = -7,     /* dtype is not FA_DTYPE_F16 / FA_DTYPE_BF16              */
@@ -156,6 +160,9 @@ typedef struct fa_params {
                                 head_dim 64 without a key bias; ignored otherwise).  The library
                                 picks it by itself when the call has at most 256 blocks of 32 query
                                 rows (one per compute unit) and max_len > 128. */
+#define FA_TUNE_BM_384 0x4u  /* 12 wavefronts x 32 query rows sharing one K/V stage (global layers of
+                                head_dim 64 without a key bias; ignored otherwise) */
+#define FA_TUNE_BM_512 0x5u  /* 8 wavefronts x 64 query rows sharing one K/V stage (same restriction) */
 #define FA_TUNE_V_AUTO 0x00u
 #define FA_TUNE_V_LDS_TRANSPOSE 0x10u /* ds_read_b64_tr_b16 operand loads */
 #define FA_TUNE_V_SCALAR 0x20u        /* 16-bit LDS reads (slow reference path) */

@@ -39,6 +39,29 @@ int resolve_strides(const int64_t in[3], int64_t out[3], int heads, int max_len,
   return FA_OK;
 }
 
+// The output rows of different (batch, head, row) must not overlap, or workgroups would race
+// on them: order the three axes by stride; each stride must cover the extent of the faster
+// axes below it (head_dim contiguous elements innermost).  Axes of extent 1 are not stepped.
+// Dense, [batch, len, heads, dim] and packed layouts pass; zero, negative or interleaving
+// strides do not.
+bool output_rows_disjoint(const int64_t st[3], int batch, int heads, int max_len, int head_dim) {
+  int64_t stride[3] = {st[0], st[1], st[2]};
+  int64_t extent[3] = {batch, heads, max_len};
+  for (int i = 0; i < 3; ++i)
+    for (int j = i + 1; j < 3; ++j)
+      if (stride[j] < stride[i]) {
+        int64_t t = stride[i]; stride[i] = stride[j]; stride[j] = t;
+        t = extent[i]; extent[i] = extent[j]; extent[j] = t;
+      }
+  long double covered = head_dim;
+  for (int i = 0; i < 3; ++i) {
+    if (extent[i] <= 1) continue;
+    if (stride[i] <= 0 || (long double)stride[i] < covered) return false;
+    covered = (long double)stride[i] * (long double)extent[i];
+  }
+  return true;
+}
+
 int choose_bm(const fa_params& p) {
   // Query rows per workgroup.  256 (two 32-row blocks per wavefront) halves LDS and
   // L2 traffic per flop, but needs enough workgroups to put two on every compute unit;
@@ -69,9 +92,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->key_bias && (reinterpret_cast<uintptr_t>(p->key_bias) & 1u)) return FA_ERR_MISALIGNED;
   if (p->key_bias_stride < 0 || (p->key_bias && p->key_bias_stride != 0 && p->key_bias_stride < p->max_len))
     return FA_ERR_BAD_SHAPE;
-  if (p->tuning & ~0x333u) return FA_ERR_BAD_TUNING;
+  if (p->tuning & ~0x337u) return FA_ERR_BAD_TUNING;
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
-  if (t_bm > FA_TUNE_BM_32 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
+  if (t_bm > FA_TUNE_BM_512 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
     return FA_ERR_BAD_TUNING;
 
   FaKernelArgs a;
@@ -81,6 +104,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->k_strides, a.ks, p->heads, p->max_len, p->head_dim))) return rc;
   if ((rc = resolve_strides(p->v_strides, a.vs, p->heads, p->max_len, p->head_dim))) return rc;
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
+  if (!output_rows_disjoint(a.os, p->batch, p->heads, p->max_len, p->head_dim)) return FA_ERR_BAD_SHAPE;
 
   // head_dim 32 and 128 run the 128-row kernel only (the tile-size hint is ignored there)
   // ... and so does a key bias unless it can ride on the pipelined global kernel
@@ -88,6 +112,12 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
   int bm = (p->head_dim != 64 || bias_on_masked_kernel) ? 128
                                    : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
+  // 384 = 12 wavefronts x 32 rows, 512 = 8 wavefronts x 64 rows: one workgroup per compute unit,
+  // global layers of head_dim 64 without a key bias on the transpose-read path
+  if (p->head_dim == 64 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR) {
+    if (t_bm == FA_TUNE_BM_384) bm = 384;
+    if (t_bm == FA_TUNE_BM_512) bm = 512;
+  }
   // Key-split kernel (32 query rows per workgroup, the wavefronts split the keys): global
   // layers of head_dim 64 without a bias whose 32-row blocks number at most one per compute
   // unit (its workgroups use a whole unit's LDS, so a second round would cost more than the
@@ -178,10 +208,10 @@ extern "C" const char* fa_strerror(int code) {
   switch (code) {
     case FA_OK: return "success";
     case FA_ERR_NULL_POINTER: return "q, k, v, o or params is NULL";
-    case FA_ERR_BAD_SHAPE: return "batch, heads, max_len or a stride is out of range";
-    case FA_ERR_BAD_HEAD_DIM: return "unsupported head_dim (supported: 64)";
+    case FA_ERR_BAD_SHAPE: return "batch, heads, max_len or a stride is out of range, or output rows overlap";
+    case FA_ERR_BAD_HEAD_DIM: return "unsupported head_dim (supported: 32, 64, 128)";
     case FA_ERR_BAD_SCALE: return "scale is not finite";
-    case FA_ERR_BAD_WINDOW: return "window must be negative (global) or >= 1";
+    case FA_ERR_BAD_WINDOW: return "window must be negative (global) or >= 1 (fa_fwd, fa_fwd_bf16)";
     case FA_ERR_MISALIGNED: return "pointer not 16-byte aligned or stride not a multiple of 8";
     case FA_ERR_BAD_DTYPE: return "dtype must be FA_DTYPE_F16 or FA_DTYPE_BF16";
     case FA_ERR_BAD_STRUCT: return "fa_params.struct_size mismatch";

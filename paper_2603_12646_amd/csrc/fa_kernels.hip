@@ -145,7 +145,9 @@ __device__ __forceinline__ float sum_xor32(float x) {
 // later LDS read wait for such a load (it cannot tell that the stage being filled and the
 // stage being read are disjoint), which would serialise the prefetch.  The caller waits
 // with wait_direct_loads() before the barrier that publishes the stage.  M0 holds the LDS
-// address; the compiler reserves M0 and reloads it before each use of its own.
+// address: M0 is a reserved register for inline asm (the compiler rejects it on a clobber list
+// with a warning that such a clobber "may lead to undefined behaviour") and is rewritten by the
+// compiler before every use of its own, so nothing of its contents is assumed after the asm.
 __device__ __forceinline__ void load16_to_lds(const void* gbase, uint32_t lane_off_bytes, void* lds_dst) {
   typedef __attribute__((address_space(3))) void lds_void;
   const uint32_t l = (uint32_t)(size_t)(lds_void*)lds_dst;
@@ -154,7 +156,14 @@ __device__ __forceinline__ void load16_to_lds(const void* gbase, uint32_t lane_o
                : "s"(l), "v"(lane_off_bytes), "s"(gbase)
                : "memory");
 }
-__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */ }
+// s_waitcnt immediate that waits for vmcnt <= N only (expcnt and lgkmcnt fields at their
+// maxima): vmcnt is bits 3:0 plus bits 15:14 of the immediate.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_direct_loads() { wait_vmcnt<0>(); }
 
 template <class T>
 __device__ __forceinline__ typename T::v8 as_v8(uint4 u) {
@@ -482,15 +491,15 @@ __device__ __forceinline__ bool locate_tile(const FaKernelArgs& a, TileCoord& tc
 }
 
 // Workgroup entirely in the padding: o = 0, lse = -inf.
-template <int BM, int D = kD>
+template <int BM, int D = kD, int THREADS = kThreads>
 __device__ __forceinline__ void zero_fill(const FaKernelArgs& a, const TileCoord& tc, uint16_t* op, float* lsep) {
   const int tid = threadIdx.x, N = a.max_len;
   constexpr int CH = D / 8;  // 16-byte chunks per row
   const int r = tid / CH, c16 = tid % CH;
-  for (int row = tc.q0 + r; row < tc.q0 + BM && row < N; row += kThreads / CH)
+  for (int row = tc.q0 + r; row < tc.q0 + BM && row < N; row += THREADS / CH)
     *(uint4*)(op + row * a.os[2] + c16 * 8) = make_uint4(0, 0, 0, 0);
   if (lsep)
-    for (int row = tc.q0 + tid; row < tc.q0 + BM && row < N; row += kThreads) lsep[row] = -INFINITY;
+    for (int row = tc.q0 + tid; row < tc.q0 + BM && row < N; row += THREADS) lsep[row] = -INFINITY;
 }
 
 template <class T, int NQB, int KS>
@@ -867,9 +876,9 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
     // Each block is 2 loads per wavefront, and loads complete in order: block t has landed
     // once at most 2 * (number of younger blocks in flight) loads are outstanding.
     const int younger = (t_hi - 1 - t < kWinStages - 2 ? t_hi - 1 - t : kWinStages - 2);
-    if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
-    else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (younger >= 2) wait_vmcnt<4>();
+    else if (younger == 1) wait_vmcnt<2>();
+    else wait_vmcnt<0>();
     scrub_block(t);
     __syncthreads();
     // stage (t-1) % kWinStages is free now: every wavefront finished block t-1 before this barrier
@@ -1174,10 +1183,10 @@ __global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKe
   // requested after it) loads are outstanding
   auto wait_for = [&](int i) {
     const int younger = issued - 1 - i;
-    if (younger >= 3) __builtin_amdgcn_s_waitcnt(0x0F70 | 24);
-    else if (younger == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 16);
-    else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (younger >= 3) wait_vmcnt<24>();
+    else if (younger == 2) wait_vmcnt<16>();
+    else if (younger == 1) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
   };
   // V rows at or beyond n are overwritten with zeros by the lanes that fetched them (0 *
   // whatever is stored in the padding must be 0); the slot is this wavefront's own
@@ -1313,18 +1322,24 @@ __global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKe
 // by |scale|, is the C operand of the block's first MFMA, so the scores arrive with the bias
 // already in them and the vector work is unchanged.  Bias values are staged per K tile
 // through a register of wavefront 0 into a small LDS array with the tile's two stages.
-template <class T, int D, int NQB, int WAVES_PER_EU, bool BIAS = false>
-__global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(const FaKernelArgs a) {
+// NW: wavefronts per workgroup (4, 8 or 12).  All of them share ONE pair of K/V stages, so the
+// tile traffic from L2 into LDS per flop falls with NW; a workgroup of 8 or 12 wavefronts
+// is meant to be alone on its compute unit (2 or 3 wavefronts per SIMD).
+template <class T, int D, int NQB, int NW, bool BIAS = false>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel(const FaKernelArgs a) {
   static_assert(D == 64 || D == 128, "pipelined kernel: head_dim 64 or 128");
-  constexpr int BM = kWaves * 32 * NQB;
+  static_assert(NW == 4 || NW == 8 || NW == 12, "4, 8 or 12 wavefronts");
+  constexpr int THREADS = NW * 64;
+  constexpr int BM = NW * 32 * NQB;
   constexpr int KS = D / 16;  // k-steps of a score block
   constexpr int DB = D / 32;  // 32-row blocks of O^T
   constexpr int SK = stride_k(D), SV = stride_v(D);
   // Two stages of 64 unpadded rows during the pipeline; the ragged tail reuses the same
   // storage with padded rows (K 64 rows, V 96 rows), which is why these arrays are sized by
-  // the padded strides.
-  static_assert(2 * kBN * SV >= 96 * SV && 2 * kBN * SK >= kWaves * epi_patch(D), "tail and epilogue reuse the stages");
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2 * kBN * SK];
+  // the padded strides; the epilogue needs one patch per wavefront in the K storage.
+  constexpr int kKElems = 2 * kBN * SK > NW * epi_patch(D) ? 2 * kBN * SK : NW * epi_patch(D);
+  static_assert(2 * kBN * SV >= 96 * SV, "the tail reuses the V stages");
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kKElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * SV];
   __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? 2 * kBN : 4];  // [stage][tile row], bias / |scale|
 
@@ -1349,7 +1364,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   };
 
   if (q0 >= n) {
-    zero_fill<BM, D>(a, tc, op, lsep);
+    zero_fill<BM, D, THREADS>(a, tc, op, lsep);
     return;
   }
 
@@ -1386,25 +1401,41 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   // fixed offset.  Halves whose rows would leave [0, N) are only ever the unused ends of
   // the pipeline (V before block 0, K after the last full block): their base is clamped,
   // their contents unused.
+  // With 8 or 12 wavefronts, wavefronts 0..7 move one half each: wavefront w rows
+  // 8 (w % 4) .. + 7 of half w / 4; the others move nothing.
   constexpr int CH = D / 8, RPI = 64 / CH, NI = 8 / RPI;
+  const int fw = wave & 3;  // row group within a half
   uint32_t koff[NI], voff[NI];  // bytes
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int dl_r = 8 * wave + i * RPI + lane / CH;  // row within a 32-row half
+    const int dl_r = 8 * fw + i * RPI + lane / CH;  // row within a 32-row half
     koff[i] = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane % CH) ^ k_swz_d<D>(dl_r)) * 8));
     voff[i] = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane % CH) ^ v_swz_d<D>(dl_r)) * 8));
   }
   // the four 32-row halves of a tile: global row bases kg / vg, LDS halves kdst / vdst
   auto fetch_halves = [&](const uint16_t* kga, const uint16_t* kgb, const uint16_t* vga, const uint16_t* vgb,
                           uint16_t* kstage, uint16_t* vstage) {
-    uint16_t* kdst = kstage + 8 * wave * D;
-    uint16_t* vdst = vstage + 8 * wave * D;
+    uint16_t* kdst = kstage + 8 * fw * D;
+    uint16_t* vdst = vstage + 8 * fw * D;
+    if (NW == 4) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      load16_to_lds(kga, koff[i], kdst + i * RPI * D);
-      load16_to_lds(kgb, koff[i], kdst + 32 * D + i * RPI * D);
-      load16_to_lds(vga, voff[i], vdst + i * RPI * D);
-      load16_to_lds(vgb, voff[i], vdst + 32 * D + i * RPI * D);
+      for (int i = 0; i < NI; ++i) {
+        load16_to_lds(kga, koff[i], kdst + i * RPI * D);
+        load16_to_lds(kgb, koff[i], kdst + 32 * D + i * RPI * D);
+        load16_to_lds(vga, voff[i], vdst + i * RPI * D);
+        load16_to_lds(vgb, voff[i], vdst + 32 * D + i * RPI * D);
+      }
+    } else if (wave < 8) {
+      const bool second = wave >= 4;  // wavefront-uniform
+      const uint16_t* kg = second ? kgb : kga;
+      const uint16_t* vg = second ? vgb : vga;
+      kdst += second ? 32 * D : 0;
+      vdst += second ? 32 * D : 0;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        load16_to_lds(kg, koff[i], kdst + i * RPI * D);
+        load16_to_lds(vg, voff[i], vdst + i * RPI * D);
+      }
     }
   };
   auto fetch = [&](int t, uint16_t* kstage, uint16_t* vstage) {
@@ -1622,7 +1653,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
   const int tail = n - nf * kBN;
   {
     const int base = nf * kBN;
-    for (int i = tid; i < 96 * CH; i += kThreads) {
+    for (int i = tid; i < 96 * CH; i += THREADS) {
       const int row = i / CH, c8 = (i % CH) * 8;
       const int jg = base - 32 + row;
       const int jc = jg < 0 ? 0 : (jg < N ? jg : N - 1);
@@ -1631,7 +1662,7 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
       *(uint4*)&lds_v[row * SV + c8] = vv;
     }
     if (tail > 0) {
-      for (int i = tid; i < 64 * CH; i += kThreads) {
+      for (int i = tid; i < 64 * CH; i += THREADS) {
         const int row = i / CH, c8 = (i % CH) * 8;
         const int jg = base + row;
         const int jc = jg < N ? jg : N - 1;
@@ -1675,58 +1706,64 @@ __global__ __launch_bounds__(kThreads, WAVES_PER_EU) void fa_fwd_global_kernel(c
 
 template <class T>
 int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
-  dim3 block(kThreads);
+  typedef void (*Kernel)(const FaKernelArgs);
   unsigned grid = (unsigned)a.total_tiles;
   if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
-  hipStream_t s = (hipStream_t)stream;
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
   // 32-key blocks a 128-row query tile of a two-sided window can touch (tiles start at multiples of 128)
   const int win_blocks = (a.wl >= 0 && a.wr >= 0) ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+  Kernel kern = nullptr;
+  unsigned threads = kThreads;
   if (a.key_bias && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
       win_blocks <= kResBlocks) {
     // additive key bias on a local layer whose key range stays resident in LDS
-    hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T, true>), dim3(grid), block, 0, s, a);
+    kern = fa_fwd_window_resident_kernel<T, true>;
   } else if (a.key_bias && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
     // additive key bias on a global layer: the pipelined kernel with the bias as MFMA C operand
-    if (a.head_dim == 128) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2, true>), dim3(grid), block, 0, s, a);
-    else if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2, true>), dim3(grid), block, 0, s, a);
+    if (a.head_dim == 128) kern = fa_fwd_global_kernel<T, 128, 1, 4, true>;
+    else if (bm == 256) kern = fa_fwd_global_kernel<T, 64, 2, 4, true>;
+    else kern = fa_fwd_global_kernel<T, 64, 1, 4, true>;
   } else if (a.key_bias) {
     // additive key bias otherwise: the masked kernel, 128-row tiles, any head_dim and window
-    if (a.head_dim == 32) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true, true>), dim3(grid), block, 0, s, a);
-    else if (a.head_dim == 64) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, true, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true, true>), dim3(grid), block, 0, s, a);
+    if (a.head_dim == 32) kern = fa_fwd_masked_kernel<T, 32, 1, true, true>;
+    else if (a.head_dim == 64) kern = fa_fwd_masked_kernel<T, 64, 1, true, true>;
+    else kern = fa_fwd_masked_kernel<T, 128, 1, true, true>;
   } else if (a.head_dim == 128 && global && v_path == 0) {
-    hipLaunchKernelGGL((fa_fwd_global_kernel<T, 128, 1, 2>), dim3(grid), block, 0, s, a);
+    kern = fa_fwd_global_kernel<T, 128, 1, 4>;
   } else if (a.head_dim != kD) {
     // head_dim 32, and the local layers of head_dim 128: the masked kernel covers every
     // mask; bm is 128 here
-    if (a.head_dim == 32) {
-      if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, true>), dim3(grid), block, 0, s, a);
-      else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 32, 1, false>), dim3(grid), block, 0, s, a);
-    } else {
-      if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, true>), dim3(grid), block, 0, s, a);
-      else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 128, 1, false>), dim3(grid), block, 0, s, a);
-    }
+    if (a.head_dim == 32) kern = v_path == 0 ? fa_fwd_masked_kernel<T, 32, 1, true> : fa_fwd_masked_kernel<T, 32, 1, false>;
+    else kern = v_path == 0 ? fa_fwd_masked_kernel<T, 128, 1, true> : fa_fwd_masked_kernel<T, 128, 1, false>;
   } else if (bm == 32) {
     // the host asks for 32-row tiles only for global layers of head_dim 64 without a bias
-    hipLaunchKernelGGL((fa_fwd_keysplit_kernel<T>), dim3(grid), block, 0, s, a);
+    kern = fa_fwd_keysplit_kernel<T>;
   } else if (global && v_path == 0) {
-    if (bm == 256) hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 2, 2>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_global_kernel<T, 64, 1, 2>), dim3(grid), block, 0, s, a);
+    if (bm == 512) {
+      kern = fa_fwd_global_kernel<T, 64, 2, 8>;
+      threads = 512;
+    } else if (bm == 384) {
+      kern = fa_fwd_global_kernel<T, 64, 1, 12>;
+      threads = 768;
+    } else if (bm == 256) {
+      kern = fa_fwd_global_kernel<T, 64, 2, 4>;
+    } else {
+      kern = fa_fwd_global_kernel<T, 64, 1, 4>;
+    }
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
-    if (win_blocks <= kResBlocks) hipLaunchKernelGGL((fa_fwd_window_resident_kernel<T>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_window_kernel<T>), dim3(grid), block, 0, s, a);
+    kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
   } else if (bm == 256) {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 2, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 2, false>), dim3(grid), block, 0, s, a);
+    kern = v_path == 0 ? fa_fwd_masked_kernel<T, 64, 2, true> : fa_fwd_masked_kernel<T, 64, 2, false>;
   } else {
-    if (v_path == 0) hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, true>), dim3(grid), block, 0, s, a);
-    else hipLaunchKernelGGL((fa_fwd_masked_kernel<T, 64, 1, false>), dim3(grid), block, 0, s, a);
+    kern = v_path == 0 ? fa_fwd_masked_kernel<T, 64, 1, true> : fa_fwd_masked_kernel<T, 64, 1, false>;
   }
-  return (int)hipGetLastError();
+  // hipLaunchKernel returns THIS launch's status; an error left by the caller's earlier HIP
+  // work stays where it is (neither reported as ours nor cleared)
+  FaKernelArgs args = a;
+  void* argv[] = {&args};
+  return (int)hipLaunchKernel((const void*)kern, dim3(grid), dim3(threads), argv, 0, (hipStream_t)stream);
 }
 
 }  // namespace

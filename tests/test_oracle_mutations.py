@@ -28,6 +28,8 @@ MUTATIONS = {
     "key bias subtracted": ("s = s + key_bias[None, :]", "s = s - key_bias[None, :]"),
     "key bias multiplied by scale": ("s = s + key_bias[None, :]", "s = s + key_bias[None, :] * scale"),
     "key bias of another batch element": ("None if key_bias is None else key_bias[b])", "None if key_bias is None else key_bias[0])"),
+    "sampled rows: key bias of another batch element": ("np.asarray(key_bias, dtype=np.float64)[b]", "np.asarray(key_bias, dtype=np.float64)[0]"),
+    "sampled rows: key bias dropped": ("scale, left, right, False, kb)", "scale, left, right, False, None)"),
     "padded rows computed": ("for r0 in range(0, n, row_block):\n                rows = np.arange(r0, min(n, r0 + row_block))",
                              "for r0 in range(0, N, row_block):\n                rows = np.arange(r0, min(N, r0 + row_block))"),
 }
@@ -47,6 +49,7 @@ BATTERY = [
     (pins.test_masked_keys_have_no_effect_even_nan, [()]),
     (pins.test_seq_len_clamping_and_empty, [()]),
     (pins.test_key_bias_brute_force, [(-1, -1, (7, 5)), (1, 2, (8, 3))]),
+    (pins.test_rows_api_key_bias_brute_force, [()]),
     (pins.test_key_bias_log_weight_equals_repeated_keys, [()]),
     (pins.test_key_bias_constant_shifts_lse_only, [()]),
     (pins.test_key_bias_minus_inf_removes_the_key, [()]),

@@ -340,6 +340,25 @@ def test_key_bias_brute_force(left, right, lens):
     assert np.array_equal(fin, np.isfinite(lse)) and np.allclose(lse[fin], lb[fin], rtol=0, atol=1e-12)
 
 
+def test_rows_api_key_bias_brute_force():
+    """The sampled-rows entry point with a bias: every batch element has its own bias row,
+    and the rows it returns are pinned to the scalar loop (not to the full oracle), for the
+    second batch element as well as the first."""
+    B, H, N, D = 3, 2, 9, 4
+    q, k, v = rand((B, H, N, D), 41), rand((B, H, N, D), 42), rand((B, H, N, D), 43)
+    bias = rand((B, N), 44) * 2.0
+    bias[1, 3] = -math.inf
+    bias[2, 0] = -65504.0
+    lens = (9, 7, 5)
+    ob, lb = brute(q, k, v, lens, 0.37, 2, 3, bias)
+    for b in range(B):
+        rows = list(range(lens[b]))
+        for h in range(H):
+            orow, lrow = attention_oracle_rows(q, k, v, b, h, rows, lens[b], 0.37, 2, 3, key_bias=bias)
+            assert np.allclose(orow, ob[b, h, rows], rtol=0, atol=1e-12), (b, h)
+            assert np.allclose(lrow, lb[b, h, rows], rtol=0, atol=1e-12), (b, h)
+
+
 def test_key_bias_log_weight_equals_repeated_keys():
     """bias_j = ln(w_j) with integer w_j is attention over a sequence in which key j (and
     its value) appears w_j times: fixes the sign of the bias and that scale does not touch it."""

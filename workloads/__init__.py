@@ -93,11 +93,15 @@ def draw(seed, batch, heads, max_len, head_dim, dtype, qk_gain=1.0, random_lens=
 
 # Workloads for the operator's other head sizes (paper Sec. 4.1.3: run-time dispatch on
 # head_dim 32 / 64 / 128).  Not among the five above: 8 heads of 128 (hidden size 1024),
-# scale 1/sqrt(128), otherwise the recipe of the 8K and 32K global workloads.
+# scale 1/sqrt(128), and 24 heads of 32, otherwise the recipe of the 8K and 32K workloads.
 NEXT_CONFIGS = {
     "d128_8k": Workload("d128_8k", 5, "fp16", 1, 8, 8192, 128, 128 ** -0.5, -1, (7900,), qk_gain=1.5),
     "d128_32k": Workload("d128_32k", 6, "bf16", 1, 8, 32768, 128, 128 ** -0.5, -1, None),
     "d128_32k_local": Workload("d128_32k_local", 6, "bf16", 1, 8, 32768, 128, 128 ** -0.5, 128, None),
+    # 24 heads of 32 (hidden size 768, as the five main workloads), scale 1/sqrt(32)
+    "d32_8k": Workload("d32_8k", 7, "fp16", 1, 24, 8192, 32, 32 ** -0.5, -1, (7900,), qk_gain=1.5),
+    "d32_32k": Workload("d32_32k", 8, "bf16", 1, 24, 32768, 32, 32 ** -0.5, -1, None),
+    "d32_32k_local": Workload("d32_32k_local", 8, "bf16", 1, 24, 32768, 32, 32 ** -0.5, 128, None),
 }
 ALL_CONFIGS = {**CONFIGS, **NEXT_CONFIGS}
 
