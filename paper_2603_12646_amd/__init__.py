@@ -15,7 +15,7 @@ __all__ = [
     "fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_workspace_bytes", "fa_strerror", "fa_version",
     "FaParams", "FaError", "load_library", "LIB_PATH",
     "FA_DTYPE_F16", "FA_DTYPE_BF16",
-    "FA_TUNE_BM_128", "FA_TUNE_BM_256", "FA_TUNE_BM_32", "FA_TUNE_BM_384", "FA_TUNE_BM_512", "FA_TUNE_V_LDS_TRANSPOSE", "FA_TUNE_V_SCALAR",
+    "FA_TUNE_BM_128", "FA_TUNE_BM_256", "FA_TUNE_BM_32", "FA_TUNE_BM_384", "FA_TUNE_BM_512", "FA_TUNE_BM_MIXED", "FA_TUNE_V_LDS_TRANSPOSE", "FA_TUNE_V_SCALAR",
     "FA_TUNE_MAP_LINEAR", "FA_TUNE_MAP_XCD",
 ]
 
@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "libfa_mi355x.so")
 
 FA_DTYPE_F16, FA_DTYPE_BF16 = 0, 1
 FA_TUNE_BM_128, FA_TUNE_BM_256, FA_TUNE_BM_32 = 0x1, 0x2, 0x3
-FA_TUNE_BM_384, FA_TUNE_BM_512 = 0x4, 0x5
+FA_TUNE_BM_384, FA_TUNE_BM_512, FA_TUNE_BM_MIXED = 0x4, 0x5, 0x6
 FA_TUNE_V_LDS_TRANSPOSE, FA_TUNE_V_SCALAR = 0x10, 0x20
 FA_TUNE_MAP_LINEAR, FA_TUNE_MAP_XCD = 0x100, 0x200
 

@@ -62,18 +62,56 @@ bool output_rows_disjoint(const int64_t st[3], int batch, int heads, int max_len
   return true;
 }
 
+// One sequence whose 128-row tiles number at most three per compute unit can take the
+// mixed-shape kernel (it splits them between 256-row and 128-row workgroups itself, from the
+// sequence length); heads <= 256 keeps the 128-row tiles left over by an odd tile count within
+// the 512 workgroup ids the launch reserves for them.
+bool mixed_fits(const fa_params& p) {
+  return p.batch == 1 && p.heads <= 256 && (((int64_t)p.max_len + 127) / 128) * p.heads <= 768;
+}
+
+// Relative time of a global layer of head_dim 64 under a tile shape, from how its workgroups
+// fill 256 compute units: full rounds of `slots` workgroups per unit cost slots * blocks each
+// (blocks = 32-row query blocks per workgroup), a partly filled last round costs less (its
+// workgroups have their SIMDs more to themselves), and `rel` is the shape's cost per block
+// relative to the 256-row shape.  Fitted to sweeps of 2K - 32K tokens x 8 - 32 heads on MI355X.
+double shape_cost(int64_t workgroups, int slots, int blocks, double rel) {
+  const int64_t per_round = 256LL * slots;
+  const int64_t full = workgroups / per_round, rest = workgroups % per_round;
+  double rounds = (double)full;
+  if (rest) {
+    const double f = (double)rest / (double)per_round;
+    double part = 1.0;
+    if (slots == 3) part = f <= 1.0 / 3 ? 0.45 : (f <= 2.0 / 3 ? 0.75 : 1.0);
+    if (slots == 2) part = f <= 0.5 ? 0.62 : 1.0;
+    rounds += part;
+  }
+  return rounds * slots * blocks * rel;
+}
+
 int choose_bm(const fa_params& p) {
-  // Query rows per workgroup.  256 (two 32-row blocks per wavefront) halves LDS and
-  // L2 traffic per flop, but needs enough workgroups to put two on every compute unit;
-  // short or few sequences, and local windows (whose key range grows with the tile),
-  // take 128.  Measured crossovers on MI355X: 8K x 12 heads is faster at 128,
-  // 16K x 36 and 32K x 12 at 256; batches of 512- to 2048-token sequences with 768 tiles of
-  // 256 rows are 1-5 % faster at 128 when their lengths are ragged, those with 1536 and
-  // more 2-7 % faster at 256.
+  // Query rows per workgroup (0 = the mixed-shape kernel).  256 (two 32-row blocks per
+  // wavefront) halves LDS and L2 traffic per flop and 512 (eight wavefronts on one K/V stage)
+  // halves the L2 traffic again, but the larger the tile the coarser the load balance over
+  // 256 compute units; local windows (whose key range grows with the tile) take 128.
   const bool windowed = p.window_left >= 0 || p.window_right >= 0;
   if (windowed) return 128;
-  const int64_t tiles256 = (((int64_t)p.max_len + 255) / 256) * p.batch * p.heads;
-  return tiles256 >= 4 * 256 ? 256 : 128;
+  const int64_t bh = (int64_t)p.batch * p.heads;
+  if (p.batch > 1 && p.max_len < 2048) {
+    // batches of short sequences (ragged lengths leave many tiles empty, which the model
+    // below cannot see).  Measured: 768 tiles of 256 rows are 1-5 % faster at 128, 1536 and
+    // more 2-7 % faster at 256.
+    return (((int64_t)p.max_len + 255) / 256) * bh >= 4 * 256 ? 256 : 128;
+  }
+  const int64_t w128 = (((int64_t)p.max_len + 127) / 128) * bh;
+  const int64_t w256 = (((int64_t)p.max_len + 255) / 256) * bh;
+  const int64_t w512 = (((int64_t)p.max_len + 511) / 512) * bh;
+  if (w128 <= 512) return 128;                      // at most two 128-row workgroups per unit
+  if (w128 <= 768 && mixed_fits(p)) return 0;       // one 256-row and one 128-row workgroup per unit
+  const double c128 = shape_cost(w128, 3, 4, 1.08), c256 = shape_cost(w256, 2, 8, 1.0),
+               c512 = shape_cost(w512, 1, 16, 0.98);
+  if (c512 < c256 && c512 < c128 && w512 <= 256) return 512;   // 512 only where one round holds the call
+  return c256 <= c128 ? 256 : 128;
 }
 
 }  // namespace
@@ -92,9 +130,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->key_bias && (reinterpret_cast<uintptr_t>(p->key_bias) & 1u)) return FA_ERR_MISALIGNED;
   if (p->key_bias_stride < 0 || (p->key_bias && p->key_bias_stride != 0 && p->key_bias_stride < p->max_len))
     return FA_ERR_BAD_SHAPE;
-  if (p->tuning & ~0x337u) return FA_ERR_BAD_TUNING;
+  if (p->tuning & ~0x337u) return FA_ERR_BAD_TUNING;  // bits of the three fields
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
-  if (t_bm > FA_TUNE_BM_512 || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
+  if (t_bm > FA_TUNE_BM_MIXED || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
     return FA_ERR_BAD_TUNING;
 
   FaKernelArgs a;
@@ -110,13 +148,19 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   // ... and so does a key bias unless it can ride on the pipelined global kernel
   const bool windowed = p->window_left >= 0 || p->window_right >= 0;
   const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
-  int bm = (p->head_dim != 64 || bias_on_masked_kernel) ? 128
-                                   : (t_bm == FA_TUNE_BM_256 ? 256 : (t_bm == FA_TUNE_BM_128 ? 128 : choose_bm(*p)));
-  // 384 = 12 wavefronts x 32 rows, 512 = 8 wavefronts x 64 rows: one workgroup per compute unit,
-  // global layers of head_dim 64 without a key bias on the transpose-read path
-  if (p->head_dim == 64 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR) {
-    if (t_bm == FA_TUNE_BM_384) bm = 384;
-    if (t_bm == FA_TUNE_BM_512) bm = 512;
+  int bm = 128;
+  if (p->head_dim == 64 && !bias_on_masked_kernel) {
+    // 384 (12 wavefronts x 32 rows), 512 (8 wavefronts x 64 rows) and the mixed launch exist for
+    // global layers without a key bias on the transpose-read path only
+    const bool plain = !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR;
+    bm = choose_bm(*p);
+    if (t_bm == FA_TUNE_BM_128) bm = 128;
+    if (t_bm == FA_TUNE_BM_256) bm = 256;
+    if (t_bm == FA_TUNE_BM_384 && plain) bm = 384;
+    if (t_bm == FA_TUNE_BM_512 && plain) bm = 512;
+    if (t_bm == FA_TUNE_BM_MIXED && plain && mixed_fits(*p)) bm = 0;
+    if (!plain && bm == 0) bm = 128;
+    if (!plain && bm == 512) bm = 256;
   }
   // Key-split kernel (32 query rows per workgroup, the wavefronts split the keys): global
   // layers of head_dim 64 without a bias whose 32-row blocks number at most one per compute
@@ -132,7 +176,8 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
     if (eligible && (t_bm == FA_TUNE_BM_32 || (t_bm == FA_TUNE_BM_AUTO && blocks32 <= 256 && p->max_len > 128)))
       bm = 32;
   }
-  const int64_t n_qtiles = ((int64_t)p->max_len + bm - 1) / bm;
+  const int tile_rows = bm == 0 ? 128 : bm;   // (the mixed launch sizes its own grid)
+  const int64_t n_qtiles = ((int64_t)p->max_len + tile_rows - 1) / tile_rows;
   const int64_t total = n_qtiles * p->batch * p->heads;
   // element count and grid must stay inside what the kernels index with
   const long double elems = (long double)p->batch * p->heads * p->max_len * p->head_dim;

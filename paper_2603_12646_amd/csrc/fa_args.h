@@ -27,7 +27,8 @@ struct FaKernelArgs {
 };
 
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
-// bm: 32 (key-split kernel), 128 or 256 query rows per workgroup; v_path: 0 = LDS transpose reads,
-// 1 = 16-bit reads.
+// bm: query rows per workgroup: 32 (key-split kernel), 128, 256, 384 (12 wavefronts), 512 (8
+// wavefronts), or 0 = 256-row and 128-row workgroups mixed (one sequence of at most 768 tiles of 128 rows over all heads); v_path: 0 = LDS
+// transpose reads, 1 = 16-bit reads.
 int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, void* stream);
 int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, void* stream);

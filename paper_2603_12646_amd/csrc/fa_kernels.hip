@@ -1325,8 +1325,24 @@ __global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKe
 // NW: wavefronts per workgroup (4, 8 or 12).  All of them share ONE pair of K/V stages, so the
 // tile traffic from L2 into LDS per flop falls with NW; a workgroup of 8 or 12 wavefronts
 // is meant to be alone on its compute unit (2 or 3 wavefronts per SIMD).
-template <class T, int D, int NQB, int NW, bool BIAS = false>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel(const FaKernelArgs a) {
+//
+// The body is a device function over LDS storage owned by the kernel that calls it, so that one
+// kernel can hold two shapes of it (see fa_fwd_global_mixed_kernel).
+template <int D, int NW>
+struct GlobalLds {
+  static constexpr int SK = stride_k(D), SV = stride_v(D);
+  // Two stages of 64 unpadded rows during the pipeline; the ragged tail reuses the same
+  // storage with padded rows (K 64 rows, V 96 rows), which is why these arrays are sized by
+  // the padded strides; the epilogue needs one patch per wavefront in the K storage.
+  static constexpr int kKElems = 2 * kBN * SK > NW * epi_patch(D) ? 2 * kBN * SK : NW * epi_patch(D);
+  static constexpr int kVElems = 2 * kBN * SV;
+  static_assert(2 * kBN * SV >= 96 * SV, "the tail reuses the V stages");
+};
+
+// tc: the workgroup's tile (tc.n already clamped into [0, max_len]).
+template <class T, int D, int NQB, int NW, bool BIAS, bool ROTATE = true>
+__device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoord& tc, uint16_t* lds_k,
+                                            uint16_t* lds_v, float* lds_bias) {
   static_assert(D == 64 || D == 128, "pipelined kernel: head_dim 64 or 128");
   static_assert(NW == 4 || NW == 8 || NW == 12, "4, 8 or 12 wavefronts");
   constexpr int THREADS = NW * 64;
@@ -1334,17 +1350,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel
   constexpr int KS = D / 16;  // k-steps of a score block
   constexpr int DB = D / 32;  // 32-row blocks of O^T
   constexpr int SK = stride_k(D), SV = stride_v(D);
-  // Two stages of 64 unpadded rows during the pipeline; the ragged tail reuses the same
-  // storage with padded rows (K 64 rows, V 96 rows), which is why these arrays are sized by
-  // the padded strides; the epilogue needs one patch per wavefront in the K storage.
-  constexpr int kKElems = 2 * kBN * SK > NW * epi_patch(D) ? 2 * kBN * SK : NW * epi_patch(D);
-  static_assert(2 * kBN * SV >= 96 * SV, "the tail reuses the V stages");
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kKElems];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2 * kBN * SV];
-  __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? 2 * kBN : 4];  // [stage][tile row], bias / |scale|
 
-  TileCoord tc;
-  if (!locate_tile<BM>(a, tc)) return;
   const int N = a.max_len, n = tc.n, q0 = tc.q0;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1512,7 +1518,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel
   // Rotating the wave priorities by hardware wave slot, one step per iteration, keeps the
   // three abreast to the end (per-wavefront stamps at 8K: finish times within 5 % of each
   // other instead of 35 %; 1-2 % off the call).
-  const bool rotate_prio = NQB == 1 && nf >= 64;
+  const bool rotate_prio = ROTATE && NQB == 1 && nf >= 64;
   int wslot = 0;
   if (rotate_prio) {
     unsigned hw_id;
@@ -1704,11 +1710,121 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel
   epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, lds_k + wave * epi_patch(D));
 }
 
+template <class T, int D, int NQB, int NW, bool BIAS = false>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel(const FaKernelArgs a) {
+  typedef GlobalLds<D, NW> L;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[L::kKElems];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[L::kVElems];
+  __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? 2 * kBN : 4];  // [stage][tile row], bias / |scale|
+  TileCoord tc;
+  if (!locate_tile<NW * 32 * NQB>(a, tc)) return;
+  global_body<T, D, NQB, NW, BIAS>(a, tc, lds_k, lds_v, lds_bias);
+}
+
+// ======================================================================================
+// Mixed-shape global kernel (head_dim 64, ONE sequence): 256-row and 128-row workgroups in one
+// launch, for calls whose 128-row tiles number between two and three per compute unit (one
+// 8K-token sequence of 12 heads: 744 tiles on 256 units).  The 128-row shape alone runs such a
+// call at three wavefronts per SIMD with three times the K/V tile traffic of the 256-row
+// shape; the 256-row shape alone leaves units with 16 query blocks beside units with 8.
+// Here the tiles are dealt as PAIRS of one 256-row workgroup (two query blocks per wavefront)
+// and one 128-row workgroup, a pair per compute unit: three blocks per SIMD on two wavefronts.
+// (A 256-row workgroup must not be alone on its unit: a single wavefront per SIMD overlaps
+// its own matrix and vector work badly and runs at less than half the rate.)
+//
+// The split is made ON THE DEVICE from the sequence length n, which the host does not know:
+// with T = ceil(n / 128) tiles per head and U = T * heads tiles in all,
+//   U <= 512 or T < 2: no 256-row workgroups (at most two 128-row workgroups per unit anyway);
+//   otherwise: A = U / 3 workgroups of 256 rows, dealt to the heads as evenly as integers allow
+//             (head h gets floor(A (h+1) / heads) - floor(A h / heads) of them, covering its
+//             FIRST rows), and 128-row workgroups on the rows after them: U - 2 A of those.
+// The host launches 256 + 512 workgroup ids whenever ceil(max_len / 128) * heads <= 768 (so
+// U <= 768 whatever n is); ids [0, 256) are the 256-row range and come first, so that the
+// dispatcher spreads them over the compute units before the 128-row workgroups follow.
+// Within each range ids are dealt round-robin to the 8 XCDs and every XCD takes a contiguous
+// eighth of the range's (head, tile) list, as in the other kernels.  Ids without a tile
+// zero-fill the tiles that lie entirely in the padding (rows at or beyond 128 T), or exit.
+// ======================================================================================
+constexpr int kMixIdsA = 256, kMixIdsB = 512;
+
+template <class T>
+__global__ __launch_bounds__(kThreads, 2) void fa_fwd_global_mixed_kernel(const FaKernelArgs a) {
+  typedef GlobalLds<kD, 4> L;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[L::kKElems];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[L::kVElems];
+  __shared__ __attribute__((aligned(16))) float lds_bias[4];
+  const int N = a.max_len, H = a.heads;
+  int n = N;
+  if (a.seq_lens) {
+    n = a.seq_lens[0];
+    n = n < 0 ? 0 : (n > N ? N : n);
+  }
+  const int tiles = (n + 127) >> 7, U = tiles * H;  // T and U of the comment above
+  const int a_tot = (U > 512 && tiles >= 2) ? U / 3 : 0;
+  const int b_tot = U - 2 * a_tot;
+  auto bnd = [&](int h) { return a_tot * h / H; };  // 256-row workgroups of heads 0 .. h-1
+  // Position of this id in its range's tile list, or, for an id that has no tile there, its
+  // index among the spare ids of the launch (spare >= 0).  With the XCD-aware order XCD x owns
+  // list entries [x per, x per + per), per = ceil(entries / 8), on ids x, x + 8, x + 16, ...
+  const int bid = (int)blockIdx.x;
+  const bool range_a = bid < kMixIdsA;
+  const int j = range_a ? bid : bid - kMixIdsA;
+  const int tot = range_a ? a_tot : b_tot, ids = range_a ? kMixIdsA : kMixIdsB;
+  const int per = (tot + 7) >> 3;
+  const int spare_a = a.map_xcd ? kMixIdsA - 8 * ((a_tot + 7) >> 3) : kMixIdsA - a_tot;
+  const int spare_b = a.map_xcd ? kMixIdsB - 8 * ((b_tot + 7) >> 3) : kMixIdsB - b_tot;
+  int t, spare = -1;
+  if (a.map_xcd) {
+    const int x = j & 7, p = j >> 3;
+    t = x * per + p;
+    if (p >= per) spare = x * (ids / 8 - per) + (p - per);
+    else if (t >= tot) return;    // at most seven ids per range: the rounding of per
+  } else {
+    t = j;
+    if (t >= tot) spare = t - tot;
+  }
+  TileCoord tc;
+  tc.b = 0;
+  tc.n = n;
+  if (spare >= 0) {
+    // tiles tiles .. ceil(max_len / 128) - 1 of every head are padding only: o = 0, lse = -inf.
+    // The spare ids share them out in a strided loop (there are normally more ids than tiles).
+    const int pad = ((N + 127) >> 7) - tiles;
+    const int spares = spare_a + spare_b;
+    for (int z = (range_a ? 0 : spare_a) + spare; z < pad * H; z += spares) {
+      tc.h = z / pad;
+      tc.qt = tiles + z % pad;
+      tc.q0 = 128 * tc.qt;
+      zero_fill<128, kD, kThreads>(a, tc, (uint16_t*)a.o + tc.h * a.os[1], a.lse ? a.lse + (int64_t)tc.h * N : nullptr);
+    }
+    return;
+  }
+  if (range_a) {
+    int h = (int)((int64_t)t * H / a_tot);
+    if (bnd(h + 1) <= t) ++h;
+    tc.h = h;
+    tc.qt = t - bnd(h);
+    tc.q0 = 256 * tc.qt;
+    global_body<T, kD, 2, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
+  } else {
+    // 128-row tiles of heads 0 .. h-1: h * tiles - 2 bnd(h), increasing in h
+    auto pre = [&](int h) { return h * tiles - 2 * bnd(h); };
+    int h = (int)((int64_t)t * H / b_tot);
+    while (h > 0 && pre(h) > t) --h;
+    while (h + 1 < H && pre(h + 1) <= t) ++h;
+    tc.h = h;
+    tc.qt = t - pre(h);
+    tc.q0 = 256 * (bnd(h + 1) - bnd(h)) + 128 * tc.qt;
+    global_body<T, kD, 1, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
+  }
+}
+
 template <class T>
 int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
   typedef void (*Kernel)(const FaKernelArgs);
   unsigned grid = (unsigned)a.total_tiles;
   if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
+  if (bm == 0) grid = kMixIdsA + kMixIdsB;
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
@@ -1741,7 +1857,9 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
     // the host asks for 32-row tiles only for global layers of head_dim 64 without a bias
     kern = fa_fwd_keysplit_kernel<T>;
   } else if (global && v_path == 0) {
-    if (bm == 512) {
+    if (bm == 0) {
+      kern = fa_fwd_global_mixed_kernel<T>;
+    } else if (bm == 512) {
       kern = fa_fwd_global_kernel<T, 64, 2, 8>;
       threads = 512;
     } else if (bm == 384) {

@@ -83,7 +83,7 @@ def test_ex_entry_point_rejects_bad_arguments():
                 stream=0, check=False)
     assert fa.fa_fwd_ex(**{**base, "dtype": 7}) == -7
     assert fa.fa_fwd_ex(**{**base, "tuning": 0x4000}) == -9
-    assert fa.fa_fwd_ex(**{**base, "tuning": 0x6}) == -9 and fa.fa_fwd_ex(**{**base, "tuning": 0x8}) == -9
+    assert fa.fa_fwd_ex(**{**base, "tuning": 0x7}) == -9 and fa.fa_fwd_ex(**{**base, "tuning": 0x8}) == -9
     # output rows that would overlap: zero / negative batch or head stride, rows inside each other
     two = {**base, "batch": 2, "heads": 2}
     assert fa.fa_fwd_ex(**{**two, "o_strides": (0, 512, 64)}) == -2

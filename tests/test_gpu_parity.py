@@ -28,13 +28,15 @@ TUNINGS = {
     "bm32_xcd": fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_XCD,
     "bm384_linear": fa.FA_TUNE_BM_384 | fa.FA_TUNE_MAP_LINEAR,
     "bm512_xcd": fa.FA_TUNE_BM_512 | fa.FA_TUNE_MAP_XCD,
+    "mixed_linear": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_LINEAR,
+    "mixed_xcd": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_XCD,
 }
 # Small global calls take the key-split kernel by themselves (at most 256 blocks of 32 query
 # rows, more than 128 tokens); the small-shape tests below therefore run three times: the
 # library's choice, the pipelined kernel forced, the key-split kernel forced; and with the
 # 12- and 8-wavefront shapes of the pipelined kernel (384 and 512 rows per workgroup).
 GLOBAL_KERNELS = {"auto": 0, "bm128": fa.FA_TUNE_BM_128, "bm32": fa.FA_TUNE_BM_32,
-                  "bm384": fa.FA_TUNE_BM_384, "bm512": fa.FA_TUNE_BM_512}
+                  "bm384": fa.FA_TUNE_BM_384, "bm512": fa.FA_TUNE_BM_512, "mixed": fa.FA_TUNE_BM_MIXED}
 
 
 # ------------------------------------------------------------------ small shapes, full compare
@@ -240,6 +242,29 @@ def test_key_split_kernel_ring_and_ragged_ends(dtype, B, H, N, lens):
     check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"key split {B}x{H}x{N}")
     o2, lse2 = run_simple(q, k, v, lens, dtype, 0.125, tuning=fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_LINEAR)
     assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("H,N,n", [(12, 8192, 7900), (12, 8192, 8192), (12, 8192, 5500), (12, 8192, 5376),
+                                   (12, 8192, 3000), (12, 8192, 0), (5, 16384, 16001), (7, 8192, 8191),
+                                   (48, 2048, 1999), (96, 1024, 1024), (200, 384, 383)])
+def test_mixed_shape_launch_covers_every_row(dtype, H, N, n):
+    """One sequence, 256-row and 128-row workgroups in one launch, split on the device from the
+    length: every row must come out exactly as the 128-row kernel computes it (the per-row
+    arithmetic is the same, so bit for bit; a tile that no workgroup took would leave NaNs),
+    with both workgroup-to-tile mappings; sampled rows also against the oracle."""
+    _, q, k, v = draw(4200 + H, 1, H, N, 64, dtype)
+    o1, lse1 = run_simple(q, k, v, [n], dtype, 0.125, tuning=fa.FA_TUNE_BM_128)
+    for mapping in (fa.FA_TUNE_MAP_XCD, fa.FA_TUNE_MAP_LINEAR):
+        o2, lse2 = run_simple(q, k, v, [n], dtype, 0.125, tuning=fa.FA_TUNE_BM_MIXED | mapping)
+        assert np.array_equal(o1, o2) and np.array_equal(lse1, lse2)
+    if n > 0:
+        rng = np.random.default_rng(H)
+        for h in (0, H // 2, H - 1):
+            rows = np.unique(np.concatenate([rng.integers(0, n, 24), [0, n - 1]]))
+            o_ref, lse_ref = attention_oracle_rows(q, k, v, 0, h, rows, n, 0.125)
+            assert np.abs(o2[0, h, rows] - o_ref).max() <= TOL[dtype]["max_abs"]
+            assert np.abs(lse2[0, h, rows] - lse_ref).max() <= LSE_TOL
 
 
 def test_key_split_merge_with_far_apart_maxima():
