@@ -67,7 +67,16 @@ def read_traffic(name):
     return None
 
 
-def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0):
+PRECONDITION_MS = 60.0      # untimed calls of the same workload before the warm-up calls
+
+
+def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0, precondition_ms=PRECONDITION_MS):
+    """Times exactly `steps` calls after `warmup` untimed ones.  Before the warm-up calls the same
+    call is repeated, untimed, for about precondition_ms of wall time: a GPU that has idled for
+    a few milliseconds (loading inputs, the host-side oracle leg) sits at a low clock and needs
+    some 25 launches of this size to come back up (measured: the first 20 calls after an idle
+    half-second take 0.25-0.26 ms each, every later hundred 0.220 ms), so a figure taken right
+    after 5 warm-up calls measures the ramp, not the kernel."""
     import torch
     import paper_2603_12646_amd as fa
 
@@ -89,6 +98,11 @@ def gpu_time(w, lens, q, k, v, steps, warmup, tuning=0):
         else:
             fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
 
+    t_pre = time.perf_counter()
+    while (time.perf_counter() - t_pre) * 1e3 < precondition_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -379,7 +393,7 @@ def cpu_baseline(w, lens, q, k, v, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
@@ -411,7 +425,9 @@ def main():
     lens, q, k, v = make_inputs(w)
     flops, nbytes = algorithmic_work(w, lens)
     wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup, args.tuning)
-    tflops = flops / (wall_ms * 1e-3) / 1e12
+    # the reported rate is taken from the HIP-event time of the timed region (the host's wall
+    # clock around the same region, which adds the final synchronisation, is reported beside it)
+    tflops = flops / (ev_ms * 1e-3) / 1e12
     hbm_bound = w.window >= 0
     if hbm_bound:
         roof = {"bound": "hbm", "achieved": nbytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
@@ -431,11 +447,12 @@ def main():
     out = {
         "metric": "attention fwd TFLOP/s (algorithmic flops; % of MFMA peak in roofline.frac); ms per call in ms_per_step",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ev_ms, "ms_per_step_host_wall_clock": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "max_len": w.max_len,
                    "head_dim": w.head_dim, "seq_lens": [int(x) for x in lens][:8], "window": w.window,
-                   "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning},
+                   "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning,
+                   "preconditioning_ms": PRECONDITION_MS},
         "roofline": roof,
     }
 
@@ -453,6 +470,11 @@ def main():
         if ceil and not hbm_bound:
             key = "mfma_f16_random_tflops" if w.dtype == "fp16" else "mfma_bf16_random_tflops"
             roof["frac_of_measured_random_data_ceiling"] = roof["achieved"] / ceil[key]
+            # the kernels' own instruction mix (matrix products + softmax vector work, operands
+            # in registers, no memory traffic) as the same program measured it
+            mkey = f"mix_{'f16' if w.dtype == 'fp16' else 'bf16'}_d{w.head_dim}_tflops"
+            if ceil.get(mkey):
+                roof["frac_of_measured_mix_ceiling"] = roof["achieved"] / ceil[mkey]
         elif ceil:
             roof["frac_of_measured_copy"] = roof["achieved"] / ceil["copy_gbs"]
 

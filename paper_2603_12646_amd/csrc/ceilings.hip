@@ -5,6 +5,16 @@
 //     power limit, so the rate an attention kernel can hope for on real data is the second
 //     number, not the data-sheet peak;
 //   * streaming copy bandwidth (1 GiB read + 1 GiB written per pass).
+//   * the attention inner loop's INSTRUCTION MIX with nothing else going on: per unit of 32 keys
+//     x 32 queries a wavefront issues D/8 matrix products (D/16 for the scores of the next
+//     unit, D/16 for the previous unit's P.V) and the softmax vector work of the current unit
+//     (16 scale-and-subtract fma, 16 exp2, 8 packed converts, the row sum, the overflow
+//     check), software-pipelined exactly as the kernels do, but with every operand fragment
+//     already in registers: no global loads, no LDS, no barriers.  Two wavefronts per SIMD,
+//     random operands.  What this loop reaches is what the kernels' arithmetic alone allows
+//     on this machine; the same loop without the matrix products gives the vector-ALU side
+//     by itself (how many units per second the softmax work alone can be issued), quoted in
+//     the same unit: 4 * D * 32 * 32 flop per unit.
 // Prints one JSON line.  Standalone program: no part of the attention path uses it.
 #include <hip/hip_runtime.h>
 #include <cstdint>
@@ -53,6 +63,97 @@ __global__ __launch_bounds__(512) void mfma_loop(const uint4* in, float* out, in
   float s = 0.f;
   for (int j = 0; j < 4; ++j)
     for (int r = 0; r < 16; ++r) s += c[j][r];
+  if (s == 12345.678f) out[0] = s;  // keeps the loop alive
+}
+
+// ---- the attention instruction mix ------------------------------------------------------
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16>
+struct Mix {
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    if constexpr (BF16)
+      return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), c, 0, 0, 0);
+    else
+      return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    if constexpr (BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector((floatx2){a, b}, bf2v));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector((floatx2){a, b}, half2v));
+  }
+};
+
+// MFMA = false: the vector work alone (the scores are declared modified by an empty asm so
+// that the compiler cannot hoist the work out of the loop).
+template <bool BF16, int D, bool MFMA>
+__global__ __launch_bounds__(256, 2) void mix_loop(const uint4* in, float* out, int iters, float c) {
+  constexpr int KS = D / 16, DB = D / 32;
+  u32x4 q[KS], ka[KS], va[2][DB];
+  for (int i = 0; i < KS; ++i) {
+    q[i] = __builtin_bit_cast(u32x4, in[(threadIdx.x * 16 + i) & 4095]);
+    ka[i] = __builtin_bit_cast(u32x4, in[(threadIdx.x * 16 + 8 + i) & 4095]);
+  }
+  for (int i = 0; i < 2 * DB; ++i) va[i / DB][i % DB] = __builtin_bit_cast(u32x4, in[(threadIdx.x * 16 + 5 * i + 3) & 4095]);
+  floatx16 oacc[DB], sA, sB;
+  for (int j = 0; j < DB; ++j)
+    for (int r = 0; r < 16; ++r) oacc[j][r] = 0.f;
+  for (int r = 0; r < 16; ++r) sA[r] = sB[r] = 0.01f * r;
+  u32x4 pA[2] = {(u32x4){0, 0, 0, 0}, (u32x4){0, 0, 0, 0}}, pB[2] = {pA[0], pA[0]};
+  float mc = 0.5f, lsum = 0.f;
+  auto unit = [&](floatx16& s_cur, floatx16& s_nxt, u32x4 (&p_prev)[2], u32x4 (&p_cur)[2]) {
+    if (MFMA) {
+      // the fragments of a new key block "arrive": the products cannot be hoisted
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(ka[ks]));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s_nxt = Mix<BF16>::mfma(ka[ks], q[ks], s_nxt);
+        oacc[ks % DB] = Mix<BF16>::mfma(va[ks / DB][ks % DB], p_prev[ks / DB], oacc[ks % DB]);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) asm volatile("" : "+v"(s_cur[r]));
+    }
+    uint32_t pk[8];
+    float l0 = 0.f, l1 = 0.f;
+    const float nmc = -mc;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * r], c, nmc));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[2 * r + 1], c, nmc));
+      pk[r] = Mix<BF16>::pack2(e0, e1);
+      if (BF16) {
+        l0 += e0;
+        l1 += e1;
+      }
+    }
+    if (!BF16) {
+#pragma unroll
+      for (int r = 0; r < 8; r += 2) {
+        l0 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, pk[r]), (half2v){1, 1}, l0, false);
+        l1 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, pk[r + 1]), (half2v){1, 1}, l1, false);
+      }
+    }
+    const float blk = l0 + l1;
+    if (__any(!(blk <= 16384.f))) mc += 1.0f;  // the overflow check (never taken here)
+    lsum += blk;
+    p_cur[0] = (u32x4){pk[0], pk[1], pk[2], pk[3]};
+    p_cur[1] = (u32x4){pk[4], pk[5], pk[6], pk[7]};
+  };
+  for (int it = 0; it < iters; ++it) {
+    unit(sA, sB, pA, pB);
+    unit(sB, sA, pB, pA);
+  }
+  float s = lsum;
+  for (int j = 0; j < DB; ++j)
+    for (int r = 0; r < 16; ++r) s += oacc[j][r];
+  for (int r = 0; r < 16; ++r) s += sA[r] + sB[r];
+  s += __builtin_bit_cast(float, pA[0][0] ^ pB[1][3]);
   if (s == 12345.678f) out[0] = s;  // keeps the loop alive
 }
 
@@ -116,6 +217,57 @@ int main() {
       const double flops = 2.0 * 32 * 32 * 16 * 16.0 * iters * (double)cus * 8 * reps;
       tf[bf][rnd] = flops / (ms * 1e-3) / 1e12;
     }
+  // the attention instruction mix: din still holds the random bf16 operands of the last pass;
+  // refill per type so that fp16 runs see fp16 bit patterns
+  double mix[2][2], valu_only[2];  // [bf16][D = 64, 128]
+  {
+    const int mix_iters = 3000;
+    const float c = 0.18033688f;  // log2(e) / 8
+    for (int bf = 0; bf < 2; ++bf) {
+      std::vector<uint16_t> h(n16 * 8, 0);
+      uint32_t x = 777u;
+      for (auto& v : h) {
+        x = x * 1664525u + 1013904223u;
+        const float f = ((int)(x >> 8) % 2001 - 1000) * 0.001f;
+        if (bf) {
+          uint32_t u;
+          __builtin_memcpy(&u, &f, 4);
+          v = (uint16_t)(u >> 16);
+        } else {
+          const _Float16 hf = (_Float16)f;
+          __builtin_memcpy(&v, &hf, 2);
+        }
+      }
+      CK(hipMemcpy(din, h.data(), h.size() * 2, hipMemcpyHostToDevice));
+      for (int which = 0; which < 3; ++which) {   // D = 64, D = 128, vector work only (D = 64)
+        auto launch = [&] {
+          const dim3 g(2 * cus), b(256);
+          if (bf) {
+            if (which == 0) mix_loop<true, 64, true><<<g, b>>>(din, dout, mix_iters, c);
+            else if (which == 1) mix_loop<true, 128, true><<<g, b>>>(din, dout, mix_iters, c);
+            else mix_loop<true, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+          } else {
+            if (which == 0) mix_loop<false, 64, true><<<g, b>>>(din, dout, mix_iters, c);
+            else if (which == 1) mix_loop<false, 128, true><<<g, b>>>(din, dout, mix_iters, c);
+            else mix_loop<false, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+          }
+        };
+        launch();
+        CK(hipDeviceSynchronize());
+        CK(hipEventRecord(e0));
+        for (int r = 0; r < reps; ++r) launch();
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        float ms;
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        const double units = 2.0 * mix_iters * (2.0 * cus) * 4 * reps;   // per wavefront 2 units per iteration
+        const double flops = units * 4.0 * (which == 1 ? 128 : 64) * 32 * 32;
+        const double t = flops / (ms * 1e-3) / 1e12;
+        if (which == 2) valu_only[bf] = t;
+        else mix[bf][which] = t;
+      }
+    }
+  }
   // copy
   const size_t bytes = (size_t)1 << 30, n = bytes / 16;
   uint4 *src, *dst;
@@ -132,8 +284,12 @@ int main() {
   CK(hipEventElapsedTime(&ms, e0, e1));
   const double copy_gbs = 2.0 * bytes * reps / (ms * 1e-3) / 1e9;
   printf("{\"compute_units\": %d, \"mfma_f16_zero_tflops\": %.1f, \"mfma_f16_random_tflops\": %.1f, "
-         "\"mfma_bf16_zero_tflops\": %.1f, \"mfma_bf16_random_tflops\": %.1f, \"copy_gbs\": %.1f}\n",
-         cus, tf[0][0], tf[0][1], tf[1][0], tf[1][1], copy_gbs);
+         "\"mfma_bf16_zero_tflops\": %.1f, \"mfma_bf16_random_tflops\": %.1f, "
+         "\"mix_f16_d64_tflops\": %.1f, \"mix_f16_d128_tflops\": %.1f, \"mix_bf16_d64_tflops\": %.1f, "
+         "\"mix_bf16_d128_tflops\": %.1f, \"softmax_valu_only_f16_d64_tflops\": %.1f, "
+         "\"softmax_valu_only_bf16_d64_tflops\": %.1f, \"copy_gbs\": %.1f}\n",
+         cus, tf[0][0], tf[0][1], tf[1][0], tf[1][1], mix[0][0], mix[0][1], mix[1][0], mix[1][1], valu_only[0],
+         valu_only[1], copy_gbs);
   CK(hipFree(src));
   CK(hipFree(dst));
   CK(hipFree(din));

@@ -98,6 +98,14 @@ struct F16 {
   static __device__ __forceinline__ float sum2(uint32_t pk, float acc) {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, pk), (half2v){1, 1}, acc, false);
   }
+  // lo + hi of a packed pair: the three-operand form with a constant zero addend, so that a
+  // chain of sums needs no register zeroed first (the compiler, given the builtin with a zero
+  // accumulator, moves 0 into a register and uses the accumulating two-operand form)
+  static __device__ __forceinline__ float sum2_first(uint32_t pk) {
+    float d;
+    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(d) : "v"(pk), "s"(0x3c003c00u));
+    return d;
+  }
   static __device__ __forceinline__ float to_float(uint16_t x) { return (float)__builtin_bit_cast(_Float16, x); }
 };
 
@@ -115,6 +123,7 @@ struct BF16 {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2v, pk),
                                            (bf2v){(__bf16)1.0f, (__bf16)1.0f}, acc, false);
   }
+  static __device__ __forceinline__ float sum2_first(uint32_t pk) { return sum2(pk, 0.f); }  // unused: bf16 sums fp32 values
   static __device__ __forceinline__ float to_float(uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); }
 };
 
@@ -303,8 +312,10 @@ __device__ __forceinline__ void prob_block(const floatx16& sv, float c, float mc
     }
   }
   if (T::kSumRounded) {
+    l0 = T::sum2_first(pk[0]);
+    l1 = T::sum2_first(pk[1]);
 #pragma unroll
-    for (int r = 0; r < 8; r += 2) {
+    for (int r = 2; r < 8; r += 2) {
       l0 = T::sum2(pk[r], l0);
       l1 = T::sum2(pk[r + 1], l1);
     }
@@ -1547,6 +1558,28 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
       ka[ks] = k_frag(&lds_k[kBN * D + 32 * D], ks);
       sA = T::mfma(ka[ks], qreg[0][ks], sA);
     }
+    if (!BIAS) {
+      // Every query block takes the maximum of its scores against key block 0 as its first
+      // reference, here, once (nothing is accumulated yet, so there is nothing to rescale): the
+      // units then need no "has this row a reference yet" test.  With a key bias block 0 can be
+      // masked out entirely, so those kernels keep the test.
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        floatx16 s0 = sA;
+        if (qb > 0) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s0[r] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) s0 = T::mfma(ka[ks], qreg[qb][ks], s0);
+        }
+        float t0 = fmaxf(s0[0], s0[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, s0[r]), s0[r + 1]);
+        const float tmax = max_xor32(t0);
+        st.m_ref[qb] = tmax;
+        st.mc[qb] = tmax == -INFINITY ? 0.f : tmax * c;
+      }
+    }
     __syncthreads();  // stage 1 is refilled during iteration 0
 
     // The probabilities are formed against the row's current reference right away; the
@@ -1590,7 +1623,7 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
       float blk;
       softmax_block(s_cur, st.mc[QB], pk, blk);
       // !(blk <= limit) also catches a NaN sum; no reference yet = first block
-      const bool trig = !(blk <= kPLimit) || st.m_ref[QB] == -INFINITY;
+      const bool trig = !(blk <= kPLimit) || (BIAS && st.m_ref[QB] == -INFINITY);
       if (__any(trig)) {
         // a row refreshes iff one of ITS two lanes tripped: no dependence on other rows
         const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;

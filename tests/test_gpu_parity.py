@@ -740,7 +740,8 @@ def test_thousands_of_tiny_sequences(window):
 # ------------------------------------------------------------------ measurement helper program
 def test_ceilings_program_reports_plausible_numbers():
     """The standalone program bench.py runs for its `ceilings` block: matrix-core rate with
-    zero and with random operands, and a 1 GiB copy."""
+    zero and with random operands, the kernels' instruction mix without memory traffic, and a
+    1 GiB copy."""
     import json
     import os
     import subprocess
@@ -754,3 +755,8 @@ def test_ceilings_program_reports_plausible_numbers():
         assert d[key] > 0
     assert 500 < d["mfma_f16_random_tflops"] <= d["mfma_f16_zero_tflops"] * 1.05 < 2500 * 1.1
     assert 1000 < d["copy_gbs"] < 8000
+    # the attention instruction mix: below the matrix-core-only rate, and head_dim 128 (twice the
+    # matrix work per exponential) above head_dim 64
+    for t in ("f16", "bf16"):
+        assert 300 < d[f"mix_{t}_d64_tflops"] < d[f"mix_{t}_d128_tflops"] < d[f"mfma_{t}_zero_tflops"] * 1.05
+        assert d[f"softmax_valu_only_{t}_d64_tflops"] > d[f"mix_{t}_d64_tflops"] * 0.8
