@@ -148,6 +148,55 @@ def per_call_times(w, lens, q, k, v, calls=50, warmup=10, flush_cache=False):
     return float(np.median(times)), float(np.min(times))
 
 
+def cold_cache_times(w, lens, q, k, v, reps=20):
+    """The bandwidth-bound local layer with the last-level cache emptied before every call.
+    Two ways of emptying it, both timed as a loop of (flush, call) pairs minus the same loop of
+    flushes alone, all on one stream with no host synchronisation inside the loops:
+      * "read": a reduction over 1 GiB reads the cache full of CLEAN lines, so the call's
+        inputs come from HBM and evicting costs nothing -- the kernel's own cold-cache time;
+      * "write": a fill of 1 GiB leaves the cache full of DIRTY lines, so the call also pays
+        for writing 256 MB of somebody else's data back to HBM while it reads its inputs.
+    Returns {"read": ms, "write": ms}."""
+    import torch
+    import paper_2603_12646_amd as fa
+
+    tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    qd, kd, vd = (torch.from_numpy(x).to(tdt).cuda() for x in (q, k, v))
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+    sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+    fn = fa.fa_fwd if w.dtype == "fp16" else fa.fa_fwd_bf16
+    junk = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+
+    def call(i):
+        fn(qd, kd, vd, o, lse, w.batch, w.heads, sl, w.max_len, w.head_dim, w.scale, w.window)
+
+    def loop_ms(body):
+        torch.cuda.synchronize()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for i in range(reps):
+            body(i)
+        stop.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop) / reps
+
+    out = {}
+    for mode, flush in (("read", lambda i: torch.sum(junk, dim=0, keepdim=True, out=sink)),
+                        ("write", lambda i: junk.fill_(float(i)))):
+        loop_ms(flush)                                     # untimed: first use of the flush kernel
+        loop_ms(lambda i: (flush(i), call(i)))
+        diffs = []
+        for _ in range(5):
+            alone = loop_ms(flush)
+            both = loop_ms(lambda i: (flush(i), call(i)))
+            diffs.append(both - alone)
+        out[mode] = float(np.median(diffs))
+    del qd, kd, vd, o, lse, junk
+    return out
+
+
 def layer_sequence_time(w, lens, q, k, v, layers=22, every=3, window=128, reps=5):
     """Attention calls of one pass through a ModernBERT-shaped encoder (paper Sec. 2.4 and
     4.1.3: local layers with a 128-token window, every third layer global): `layers` calls
@@ -503,12 +552,14 @@ def main():
             others[name] = {"ms_per_call": ems, "tflops": of / (ems * 1e-3) / 1e12,
                             "frac_mfma_peak": of / (ems * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                             "algorithmic_gbs": ob / (ems * 1e-3) / 1e9, "dtype": ow.dtype, "head_dim": ow.head_dim}
-            if ow.window >= 0 and ow.head_dim == 64:
+            if ow.window >= 0:
                 # bandwidth-bound layer: back-to-back calls find part of their 200 MB in the
-                # last-level cache; also time it with the cache flushed between calls
-                cold_med, cold_min = per_call_times(ow, ol, oq, ok_, ov, calls=20, warmup=3, flush_cache=True)
-                others[name]["ms_per_call_cache_flushed_median"] = cold_med
-                others[name]["algorithmic_gbs_cache_flushed"] = ob / (cold_med * 1e-3) / 1e9
+                # last-level cache; also time it with the cache emptied before every call
+                cold = cold_cache_times(ow, ol, oq, ok_, ov)
+                others[name]["ms_per_call_cold_cache_clean"] = cold["read"]
+                others[name]["algorithmic_gbs_cold_cache_clean"] = ob / (cold["read"] * 1e-3) / 1e9
+                others[name]["ms_per_call_cold_cache_dirty"] = cold["write"]
+                others[name]["algorithmic_gbs_cold_cache_dirty"] = ob / (cold["write"] * 1e-3) / 1e9
             del oq, ok_, ov
         out["config"]["other_workloads"] = others
         # one encoder pass worth of attention calls (22 layers, every third global) at 8K and 32K

@@ -152,7 +152,7 @@ typedef struct fa_params {
 } fa_params;
 
 /* tuning word: bits 0-3 query rows per workgroup, bits 4-7 V-operand path,
-   bits 8-11 workgroup-to-tile mapping. */
+   bits 8-11 workgroup-to-tile mapping, bits 12-15 window kernel. */
 #define FA_TUNE_BM_AUTO 0x0u
 #define FA_TUNE_BM_128 0x1u  /* 4 wavefronts x 32 query rows  */
 #define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows (head_dim 64 only; ignored otherwise) */
@@ -172,6 +172,11 @@ typedef struct fa_params {
 #define FA_TUNE_MAP_AUTO 0x000u
 #define FA_TUNE_MAP_LINEAR 0x100u     /* workgroup id = tile id */
 #define FA_TUNE_MAP_XCD 0x200u        /* tiles of one head kept on one XCD's L2 */
+
+#define FA_TUNE_WIN_AUTO 0x0000u
+#define FA_TUNE_WIN_PIPELINED 0x1000u /* local layers: never the two-phase kernel (K, then V, through one
+                                         LDS region; four workgroups per compute unit), i.e. the
+                                         pipelined kernels with K and V resident or in a ring */
 
 int fa_fwd_ex(const fa_params* params);
 

@@ -130,7 +130,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->key_bias && (reinterpret_cast<uintptr_t>(p->key_bias) & 1u)) return FA_ERR_MISALIGNED;
   if (p->key_bias_stride < 0 || (p->key_bias && p->key_bias_stride != 0 && p->key_bias_stride < p->max_len))
     return FA_ERR_BAD_SHAPE;
-  if (p->tuning & ~0x337u) return FA_ERR_BAD_TUNING;  // bits of the three fields
+  if (p->tuning & ~0x1337u) return FA_ERR_BAD_TUNING;  // bits of the four fields
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
   if (t_bm > FA_TUNE_BM_MIXED || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
     return FA_ERR_BAD_TUNING;
@@ -207,8 +207,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   a.xcd_per = (int32_t)per;
   const int v_path = t_v == FA_TUNE_V_SCALAR ? 1 : 0;
 
-  return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, p->stream)
-                                  : fa_launch_bf16(a, bm, v_path, p->stream);
+  const int win_kernel = (p->tuning & FA_TUNE_WIN_PIPELINED) ? 1 : 0;
+  return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, win_kernel, p->stream)
+                                  : fa_launch_bf16(a, bm, v_path, win_kernel, p->stream);
 }
 
 static int fwd_simple(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,

@@ -1106,6 +1106,179 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 }
 
 // ======================================================================================
+// Two-phase window kernel: local layers of head_dim 64 in which a wavefront's 32 queries see at
+// most kTwoPhaseBlocks 32-key blocks (the paper's 63/64 window: five) and a 128-row tile at
+// most kResBlocks.  Such a layer is bound by memory traffic (64 flop per byte), and what
+// decides its speed is how many workgroups a compute unit holds at once: workgroups load,
+// compute and store one after the other, so the more of them are resident, the more of the
+// time the memory system has requests in flight.  With K and V both resident in LDS (64 KB,
+// the kernel above) that is two workgroups per unit.  Here ONE 32 KB region holds the K
+// blocks first and the V blocks afterwards, which allows four workgroups per unit:
+//   phase 1: K blocks arrive by direct loads; every wavefront forms the scores of ALL its
+//            visible blocks (up to 5 x 16 accumulator registers per lane: a whole window row
+//            fits in registers), barrier;
+//   phase 2: the V blocks are requested into the same region, and while they travel the
+//            wavefront turns its scores into probabilities - an ordinary softmax over the
+//            whole row: exact maximum, no running reference, nothing to rescale;
+//   phase 3: V has landed (barrier): O^T = sum over blocks of V^T P^T, epilogue.
+// No software pipeline inside a wavefront: the four wavefronts a SIMD holds are in different
+// phases and fill each other's gaps.  (Touching V's cache lines at the start, so that the
+// phase-2 request finds them in cache, measured 8 % slower on a cold cache: not done.)
+// ======================================================================================
+constexpr int kTwoPhaseBlocks = 5;
+
+template <class T>
+__global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(const FaKernelArgs a) {
+  constexpr int BM = kWaves * 32;
+  constexpr int kBlk = 32 * kD;  // elements per block
+  static_assert(kResBlocks * kBlk >= kWaves * kEpiPatch, "the region doubles as the epilogue patches");
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kResBlocks * kBlk];
+
+  TileCoord tc;
+  if (!locate_tile<BM, false>(a, tc)) return;  // tc.n still as loaded: see below
+  const int N = a.max_len, q0 = tc.q0;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  const uint16_t* qp = (const uint16_t*)a.q + tc.b * a.qs[0] + tc.h * a.qs[1];
+  const uint16_t* kp = (const uint16_t*)a.k + tc.b * a.ks[0] + tc.h * a.ks[1];
+  const uint16_t* vp = (const uint16_t*)a.v + tc.b * a.vs[0] + tc.h * a.vs[1];
+  uint16_t* op = (uint16_t*)a.o + tc.b * a.os[0] + tc.h * a.os[1];
+  float* lsep = a.lse ? a.lse + ((int64_t)tc.b * a.heads + tc.h) * N : nullptr;
+
+  // Key blocks this tile can touch, from the tile position and the tensor length alone (the
+  // sequence length is looked at only after the loads are on their way).  Block b lives in
+  // slot b - b_lo; blocks past the sequence end are fetched and never read.
+  const int lo = q0 - a.wl > 0 ? q0 - a.wl : 0;
+  const int b_lo = lo >> 5;
+  int b_hi_ld = (q0 + BM + a.wr + 31) >> 5;
+  b_hi_ld = b_hi_ld < ((N + 31) >> 5) ? b_hi_ld : ((N + 31) >> 5);
+  if (b_hi_ld > b_lo + kResBlocks) b_hi_ld = b_lo + kResBlocks;  // never true for the windows the host routes here
+
+  // Wavefront w moves rows 8w..8w+7 of every block (one 1 KB load per block).  A lane's row is
+  // clamped to the last row of the tensor (rows >= n are masked or zeroed below), so its
+  // global offset is a per-lane 32-bit byte offset from the slice.
+  const int dl_r = 8 * wave + (lane >> 3);
+  auto request_blocks = [&](const uint16_t* base, uint32_t row_bytes, int swz) {
+    const uint32_t chunk = 2u * (uint32_t)(((lane & 7) ^ swz) * 8);
+#pragma unroll
+    for (int i = 0; i < kResBlocks; ++i) {
+      if (b_lo + i < b_hi_ld) {
+        const int jg = (b_lo + i) * 32 + dl_r;
+        const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+        load16_to_lds(base, jc * row_bytes + chunk, &lds[i * kBlk + 8 * wave * kD]);
+      }
+    }
+  };
+  request_blocks(kp, 2u * (uint32_t)a.ks[2], k_swz(dl_r));
+
+  const int qw0 = q0 + wave * 32;
+  typename T::v8 qreg[1][4];
+  load_q<T, 1>(a, qp, qw0, lane, qreg);
+  // only now the sequence length
+  const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
+  tc.n = n;
+  if (q0 >= n) {
+    wait_direct_loads();  // the loads write this workgroup's LDS: they must land before it ends
+    zero_fill<BM>(a, tc, op, lsep);
+    return;
+  }
+  const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
+  const int hi = q_last + a.wr + 1 < n ? q_last + a.wr + 1 : n;
+  int b_hi = (hi + 31) >> 5;  // blocks [b_lo, b_hi) hold visible keys
+  if (b_hi > b_hi_ld) b_hi = b_hi_ld;
+  const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
+  const bool wave_has_rows = qw_last >= qw0;
+  const int ig = qw0 + l32;
+  const int jlo = ig - a.wl > 0 ? ig - a.wl : 0;
+  const int jhi = ig + a.wr < n - 1 ? ig + a.wr : n - 1;
+  const float c = a.c;
+  // blocks this wavefront's queries can see: fb .. fb + cnt - 1, cnt <= kTwoPhaseBlocks
+  int fb = (qw0 - a.wl) >> 5;
+  fb = fb < b_lo ? b_lo : fb;
+  int lb = (qw_last + a.wr) >> 5;
+  lb = lb > b_hi - 1 ? b_hi - 1 : lb;
+  int cnt = wave_has_rows ? lb - fb + 1 : 0;
+  cnt = cnt > kTwoPhaseBlocks ? kTwoPhaseBlocks : cnt;  // (the host routes no wider window here)
+
+  // ---- phase 1: scores of every visible block
+  wait_direct_loads();
+  __syncthreads();
+  floatx16 sc[kTwoPhaseBlocks];
+#pragma unroll
+  for (int i = 0; i < kTwoPhaseBlocks; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
+    if (i < cnt) {
+      const uint16_t* kblk = &lds[(fb + i - b_lo) * kBlk];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) sc[i] = T::mfma(load_k_frag_swz<T>(kblk, l32, hh, ks), qreg[0][ks], sc[i]);
+    }
+  }
+  __syncthreads();  // every wavefront has its K fragments out of the region
+
+  // ---- phase 2: request V into the same region; softmax meanwhile
+  request_blocks(vp, 2u * (uint32_t)a.vs[2], v_swz(dl_r));
+  uint32_t vis[kTwoPhaseBlocks];
+  float t0 = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kTwoPhaseBlocks; ++i) {
+    vis[i] = 0;
+    if (i < cnt) {
+      const int kb0 = (fb + i) * 32;
+      // blocks every valid query of the wavefront sees completely need no mask work
+      const bool interior = kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr;
+      vis[i] = interior ? 0xFFFFu : visible_bits(kb0, hh, jlo, jhi);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis[i] >> r & 1) ? sc[i][r] : -INFINITY);
+    }
+  }
+  RowState<1> st;
+  init_state(st);
+  const float tmax = max_xor32(t0);
+  st.m_ref[0] = tmax;
+  st.mc[0] = tmax == -INFINITY ? 0.f : tmax * c;   // a row without a visible key: every p is masked to 0
+  typename T::v8 pr[kTwoPhaseBlocks][2];
+#pragma unroll
+  for (int i = 0; i < kTwoPhaseBlocks; ++i) {
+    if (i < cnt) {
+      uint32_t pk[8];
+      float blk;
+      if (vis[i] == 0xFFFFu) prob_block<T, false>(sc[i], c, st.mc[0], vis[i], pk, blk);
+      else prob_block<T, true>(sc[i], c, st.mc[0], vis[i], pk, blk);
+      st.lsum[0] += blk;
+      pr[i][0] = as_v8<T>(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+      pr[i][1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
+    } else {
+      pr[i][0] = pr[i][1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+    }
+  }
+
+  // ---- phase 3: V has landed
+  wait_direct_loads();
+  // V rows at or beyond n are overwritten with zeros by the lanes that fetched them
+  // (0 * whatever is stored in the padding must be 0); only the last block can have any
+  {
+    const int i = b_hi - 1 - b_lo;
+    if ((b_hi - 1) * 32 + dl_r >= n) *(uint4*)&lds[i * kBlk + dl_r * kD + (lane & 7) * 8] = make_uint4(0, 0, 0, 0);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kTwoPhaseBlocks; ++i) {
+    if (i < cnt) {
+      const uint16_t* vblk = &lds[(fb + i - b_lo) * kBlk];
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+        st.oacc[0][x & 1] = T::mfma(load_vt_frag_swz<T>(vblk, lane, x >> 1, x & 1), pr[i][x >> 1], st.oacc[0][x & 1]);
+    }
+  }
+  __syncthreads();  // all blocks consumed: the region becomes the epilogue patches
+  epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds + wave * kEpiPatch);
+}
+
+// ======================================================================================
 // Key-split kernel: global layers with very few query tiles (a single short sequence).
 // With 128-row tiles one 512-token sequence of 12 heads is 48 workgroups on 256 compute
 // units, one wavefront per SIMD walking 16 key blocks one after the other.  Here a
@@ -1853,7 +2026,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_global_mixed_kernel(const 
 }
 
 template <class T>
-int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
+int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
   typedef void (*Kernel)(const FaKernelArgs);
   unsigned grid = (unsigned)a.total_tiles;
   if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
@@ -1904,7 +2077,10 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
       kern = fa_fwd_global_kernel<T, 64, 1, 4>;
     }
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
-    kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
+    // 32-key blocks the 32 queries of one wavefront can see (they start at a multiple of 32)
+    const int wave_blocks = (a.wl >= 0 && a.wr >= 0) ? (31 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+    if (win_blocks <= kResBlocks && wave_blocks <= kTwoPhaseBlocks && win_kernel != 1) kern = fa_fwd_window_twophase_kernel<T>;
+    else kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
   } else if (bm == 256) {
     kern = v_path == 0 ? fa_fwd_masked_kernel<T, 64, 2, true> : fa_fwd_masked_kernel<T, 64, 2, false>;
   } else {
@@ -1919,9 +2095,9 @@ int launch(const FaKernelArgs& a, int bm, int v_path, void* stream) {
 
 }  // namespace
 
-int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, void* stream) {
-  return launch<F16>(a, bm, v_path, stream);
+int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
+  return launch<F16>(a, bm, v_path, win_kernel, stream);
 }
-int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, void* stream) {
-  return launch<BF16>(a, bm, v_path, stream);
+int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
+  return launch<BF16>(a, bm, v_path, win_kernel, stream);
 }

@@ -28,6 +28,8 @@ TUNINGS = {
     "bm32_xcd": fa.FA_TUNE_BM_32 | fa.FA_TUNE_MAP_XCD,
     "bm384_linear": fa.FA_TUNE_BM_384 | fa.FA_TUNE_MAP_LINEAR,
     "bm512_xcd": fa.FA_TUNE_BM_512 | fa.FA_TUNE_MAP_XCD,
+    "win_pipelined": fa.FA_TUNE_WIN_PIPELINED,
+    "win_pipelined_linear": fa.FA_TUNE_WIN_PIPELINED | fa.FA_TUNE_MAP_LINEAR,
     "mixed_linear": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_LINEAR,
     "mixed_xcd": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_XCD,
 }
