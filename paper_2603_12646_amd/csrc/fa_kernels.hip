@@ -236,10 +236,33 @@ __device__ __forceinline__ int v_swz(int r) { return 4 * ((r >> 1) & 1) + 2 * ((
 //   V: 4 rows x 4 chunks, or 8 rows x 2 chunks, per 32 lanes.
 __device__ __forceinline__ int k_swz128(int r) { return 2 * (r & 7) + ((r >> 3) & 1); }
 __device__ __forceinline__ int v_swz128(int r) { return 4 * (r & 3) + 2 * ((r >> 2) & 1); }
+// head_dim 32: a 64-byte row has 4 chunk positions and four rows cover the banks once.
+//   K: rows r, r+4, r+8, r+12 share their banks, so at one chunk they need four different
+//      positions, and rows r, r+4 at a chunk pair (2 ks, 2 ks + 1) two disjoint pairs.
+//   V: 4 rows x 4 chunks per 32 lanes is 256 contiguous bytes: no swizzle needed.
+__device__ __forceinline__ int k_swz32(int r) { return 2 * ((r >> 2) & 1) + ((r >> 3) & 1); }
 template <int D>
-__device__ __forceinline__ int k_swz_d(int r) { return D == 128 ? k_swz128(r) : k_swz(r); }
+__device__ __forceinline__ int k_swz_d(int r) { return D == 128 ? k_swz128(r) : (D == 32 ? k_swz32(r) : k_swz(r)); }
 template <int D>
-__device__ __forceinline__ int v_swz_d(int r) { return D == 128 ? v_swz128(r) : v_swz(r); }
+__device__ __forceinline__ int v_swz_d(int r) { return D == 128 ? v_swz128(r) : (D == 32 ? 0 : v_swz(r)); }
+// Operand fragments out of a swizzled 32-row block of any head_dim (row = D elements).
+template <class T, int D>
+__device__ __forceinline__ typename T::v8 load_k_frag_swz_d(const uint16_t* kblk, int l32, int hh, int ks) {
+  return as_v8<T>(*(const uint4*)&kblk[l32 * D + (((2 * ks + hh) ^ k_swz_d<D>(l32)) * 8)]);
+}
+template <class T, int D>
+__device__ __forceinline__ typename T::v8 load_vt_frag_swz_d(const uint16_t* vblk, int lane, int ks2, int db) {
+  const int hh = lane >> 5, p16 = lane & 15, g = (lane >> 4) & 1;
+  const int row = ks2 * 16 + 4 * hh + (p16 >> 2);  // (rows row and row + 8 have the same swizzle)
+  const int off = (((4 * db + 2 * g + ((p16 & 3) >> 1)) ^ v_swz_d<D>(row)) * 8) + (p16 & 1) * 4;
+  typedef __attribute__((address_space(3))) shortx4 lds_s4;
+  const shortx4 x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[row * D + off]);
+  const shortx4 x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)&vblk[(row + 8) * D + off]);
+  shortx8 x;
+  x[0] = x0[0]; x[1] = x0[1]; x[2] = x0[2]; x[3] = x0[3];
+  x[4] = x1[0]; x[5] = x1[1]; x[6] = x1[2]; x[7] = x1[3];
+  return __builtin_bit_cast(typename T::v8, x);
+}
 
 template <class T>
 __device__ __forceinline__ typename T::v8 load_k_frag_swz(const uint16_t* kblk, int l32, int hh, int ks) {
@@ -1127,11 +1150,12 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 // ======================================================================================
 constexpr int kTwoPhaseBlocks = 5;
 
-template <class T>
-__global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(const FaKernelArgs a) {
+template <class T, int D>
+__global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twophase_kernel(const FaKernelArgs a) {
   constexpr int BM = kWaves * 32;
-  constexpr int kBlk = 32 * kD;  // elements per block
-  static_assert(kResBlocks * kBlk >= kWaves * kEpiPatch, "the region doubles as the epilogue patches");
+  constexpr int KS = D / 16, DB = D / 32;
+  constexpr int kBlk = 32 * D;  // elements per block
+  static_assert(kResBlocks * kBlk >= kWaves * epi_patch(D), "the region doubles as the epilogue patches");
   __shared__ __attribute__((aligned(16))) uint16_t lds[kResBlocks * kBlk];
 
   TileCoord tc;
@@ -1157,32 +1181,39 @@ __global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(con
   b_hi_ld = b_hi_ld < ((N + 31) >> 5) ? b_hi_ld : ((N + 31) >> 5);
   if (b_hi_ld > b_lo + kResBlocks) b_hi_ld = b_lo + kResBlocks;  // never true for the windows the host routes here
 
-  // Wavefront w moves rows 8w..8w+7 of every block (one 1 KB load per block).  A lane's row is
-  // clamped to the last row of the tensor (rows >= n are masked or zeroed below), so its
-  // global offset is a per-lane 32-bit byte offset from the slice.
-  const int dl_r = 8 * wave + (lane >> 3);
-  auto request_blocks = [&](const uint16_t* base, uint32_t row_bytes, int swz) {
-    const uint32_t chunk = 2u * (uint32_t)(((lane & 7) ^ swz) * 8);
+  // A direct load moves 1 KB = RPL rows of a block (lane L: row L / CH, chunk position L % CH of
+  // the load), so a block is LPB loads; the loads of all blocks, numbered block * LPB + part,
+  // are dealt round-robin to the four wavefronts.  A lane's row is clamped to the last row of
+  // the tensor (rows >= n are masked or zeroed below), so its global offset is a per-lane
+  // 32-bit byte offset from the slice.
+  constexpr int CH = D / 8, RPL = 64 / CH, LPB = 32 / RPL;   // D = 32: 4, 16, 2;  64: 8, 8, 4;  128: 16, 4, 8
+  constexpr int kLoadsPerWave = kResBlocks * LPB / kWaves;
+  auto request_blocks = [&](const uint16_t* base, uint32_t row_bytes, bool is_k) {
 #pragma unroll
-    for (int i = 0; i < kResBlocks; ++i) {
+    for (int x = 0; x < kLoadsPerWave; ++x) {
+      const int j = wave + kWaves * x;          // wavefront-uniform
+      const int i = j / LPB, part = j % LPB;
       if (b_lo + i < b_hi_ld) {
-        const int jg = (b_lo + i) * 32 + dl_r;
+        const int r = part * RPL + lane / CH;   // row within the block
+        const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
+        const int jg = (b_lo + i) * 32 + r;
         const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
-        load16_to_lds(base, jc * row_bytes + chunk, &lds[i * kBlk + 8 * wave * kD]);
+        load16_to_lds(base, jc * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8), &lds[i * kBlk + part * RPL * D]);
       }
     }
   };
-  request_blocks(kp, 2u * (uint32_t)a.ks[2], k_swz(dl_r));
+  request_blocks(kp, 2u * (uint32_t)a.ks[2], true);
 
   const int qw0 = q0 + wave * 32;
-  typename T::v8 qreg[1][4];
+  typename T::v8 qreg[1][KS];
   load_q<T, 1>(a, qp, qw0, lane, qreg);
+
   // only now the sequence length
   const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
   tc.n = n;
   if (q0 >= n) {
     wait_direct_loads();  // the loads write this workgroup's LDS: they must land before it ends
-    zero_fill<BM>(a, tc, op, lsep);
+    zero_fill<BM, D>(a, tc, op, lsep);
     return;
   }
   const int q_last = (q0 + BM < n ? q0 + BM : n) - 1;
@@ -1214,13 +1245,13 @@ __global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(con
     if (i < cnt) {
       const uint16_t* kblk = &lds[(fb + i - b_lo) * kBlk];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) sc[i] = T::mfma(load_k_frag_swz<T>(kblk, l32, hh, ks), qreg[0][ks], sc[i]);
+      for (int ks = 0; ks < KS; ++ks) sc[i] = T::mfma(load_k_frag_swz_d<T, D>(kblk, l32, hh, ks), qreg[0][ks], sc[i]);
     }
   }
   __syncthreads();  // every wavefront has its K fragments out of the region
 
   // ---- phase 2: request V into the same region; softmax meanwhile
-  request_blocks(vp, 2u * (uint32_t)a.vs[2], v_swz(dl_r));
+  request_blocks(vp, 2u * (uint32_t)a.vs[2], false);
   uint32_t vis[kTwoPhaseBlocks];
   float t0 = -INFINITY;
 #pragma unroll
@@ -1235,7 +1266,7 @@ __global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(con
       for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis[i] >> r & 1) ? sc[i][r] : -INFINITY);
     }
   }
-  RowState<1> st;
+  RowState<1, D> st;
   init_state(st);
   const float tmax = max_xor32(t0);
   st.m_ref[0] = tmax;
@@ -1262,7 +1293,14 @@ __global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(con
   // (0 * whatever is stored in the padding must be 0); only the last block can have any
   {
     const int i = b_hi - 1 - b_lo;
-    if ((b_hi - 1) * 32 + dl_r >= n) *(uint4*)&lds[i * kBlk + dl_r * kD + (lane & 7) * 8] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int x = 0; x < kLoadsPerWave; ++x) {
+      const int j = wave + kWaves * x;
+      if (j / LPB == i) {
+        const int r = (j % LPB) * RPL + lane / CH;
+        if ((b_hi - 1) * 32 + r >= n) *(uint4*)&lds[i * kBlk + r * D + (lane % CH) * 8] = make_uint4(0, 0, 0, 0);
+      }
+    }
   }
   __syncthreads();
 #pragma unroll
@@ -1270,12 +1308,14 @@ __global__ __launch_bounds__(kThreads, 4) void fa_fwd_window_twophase_kernel(con
     if (i < cnt) {
       const uint16_t* vblk = &lds[(fb + i - b_lo) * kBlk];
 #pragma unroll
-      for (int x = 0; x < 4; ++x)
-        st.oacc[0][x & 1] = T::mfma(load_vt_frag_swz<T>(vblk, lane, x >> 1, x & 1), pr[i][x >> 1], st.oacc[0][x & 1]);
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          st.oacc[0][db] = T::mfma(load_vt_frag_swz_d<T, D>(vblk, lane, ks2, db), pr[i][ks2], st.oacc[0][db]);
     }
   }
   __syncthreads();  // all blocks consumed: the region becomes the epilogue patches
-  epilogue<T, 1>(a, st, op, lsep, qw0, n, lane, lds + wave * kEpiPatch);
+  epilogue<T, 1, D>(a, st, op, lsep, qw0, n, lane, lds + wave * epi_patch(D));
 }
 
 // ======================================================================================
@@ -2036,9 +2076,16 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;
   // 32-key blocks a 128-row query tile of a two-sided window can touch (tiles start at multiples of 128)
   const int win_blocks = (a.wl >= 0 && a.wr >= 0) ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+  // 32-key blocks the 32 queries of one wavefront can see (they start at a multiple of 32)
+  const int wave_blocks = (a.wl >= 0 && a.wr >= 0) ? (31 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
   Kernel kern = nullptr;
   unsigned threads = kThreads;
-  if (a.key_bias && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
+  if (!a.key_bias && !global && v_path == 0 && bm == 128 && slice_fits_32bit && win_blocks <= kResBlocks &&
+      wave_blocks <= kTwoPhaseBlocks && win_kernel != 1) {
+    // local layer with a narrow two-sided window (the paper's 63/64), any head_dim
+    kern = a.head_dim == 32 ? fa_fwd_window_twophase_kernel<T, 32>
+                            : (a.head_dim == 64 ? fa_fwd_window_twophase_kernel<T, 64> : fa_fwd_window_twophase_kernel<T, 128>);
+  } else if (a.key_bias && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
       win_blocks <= kResBlocks) {
     // additive key bias on a local layer whose key range stays resident in LDS
     kern = fa_fwd_window_resident_kernel<T, true>;
@@ -2055,8 +2102,8 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
   } else if (a.head_dim == 128 && global && v_path == 0) {
     kern = fa_fwd_global_kernel<T, 128, 1, 4>;
   } else if (a.head_dim != kD) {
-    // head_dim 32, and the local layers of head_dim 128: the masked kernel covers every
-    // mask; bm is 128 here
+    // head_dim 32 global layers, and wide or one-sided windows of head_dim 32 / 128: the masked
+    // kernel covers every mask; bm is 128 here
     if (a.head_dim == 32) kern = v_path == 0 ? fa_fwd_masked_kernel<T, 32, 1, true> : fa_fwd_masked_kernel<T, 32, 1, false>;
     else kern = v_path == 0 ? fa_fwd_masked_kernel<T, 128, 1, true> : fa_fwd_masked_kernel<T, 128, 1, false>;
   } else if (bm == 32) {
@@ -2077,10 +2124,7 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
       kern = fa_fwd_global_kernel<T, 64, 1, 4>;
     }
   } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
-    // 32-key blocks the 32 queries of one wavefront can see (they start at a multiple of 32)
-    const int wave_blocks = (a.wl >= 0 && a.wr >= 0) ? (31 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
-    if (win_blocks <= kResBlocks && wave_blocks <= kTwoPhaseBlocks && win_kernel != 1) kern = fa_fwd_window_twophase_kernel<T>;
-    else kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
+    kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
   } else if (bm == 256) {
     kern = v_path == 0 ? fa_fwd_masked_kernel<T, 64, 2, true> : fa_fwd_masked_kernel<T, 64, 2, false>;
   } else {

@@ -327,7 +327,7 @@ def test_valid_call_returns_zero_and_bad_call_leaves_output_untouched():
 
 # ------------------------------------------------------------------ head_dim 32 and 128
 HD_TUNINGS = {"auto": 0, "scalar_linear": fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_LINEAR,
-              "bm256_hint_ignored": fa.FA_TUNE_BM_256}
+              "bm256_hint_ignored": fa.FA_TUNE_BM_256, "win_pipelined": fa.FA_TUNE_WIN_PIPELINED}
 
 
 @pytest.mark.parametrize("tuning", sorted(HD_TUNINGS))
