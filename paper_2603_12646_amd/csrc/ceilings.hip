@@ -10,8 +10,8 @@
 //     unit, D/16 for the previous unit's P.V) and the softmax vector work of the current unit
 //     (16 scale-and-subtract fma, 16 exp2, 8 packed converts, the row sum, the overflow
 //     check), software-pipelined exactly as the kernels do, but with every operand fragment
-//     already in registers: no global loads, no LDS, no barriers.  Two wavefronts per SIMD,
-//     random operands.  What this loop reaches is what the kernels' arithmetic alone allows
+//     already in registers: no global loads, no LDS, no barriers.  Two, three and four
+//     wavefronts per SIMD (the best is reported; head_dim 128 fits two), random operands.  What this loop reaches is what the kernels' arithmetic alone allows
 //     on this machine; the same loop without the matrix products gives the vector-ALU side
 //     by itself (how many units per second the softmax work alone can be issued), quoted in
 //     the same unit: 4 * D * 32 * 32 flop per unit.
@@ -89,7 +89,7 @@ struct Mix {
 // MFMA = false: the vector work alone (the scores are declared modified by an empty asm so
 // that the compiler cannot hoist the work out of the loop).
 template <bool BF16, int D, bool MFMA>
-__global__ __launch_bounds__(256, 2) void mix_loop(const uint4* in, float* out, int iters, float c) {
+__global__ __launch_bounds__(256, D == 128 ? 2 : 4) void mix_loop(const uint4* in, float* out, int iters, float c) {
   constexpr int KS = D / 16, DB = D / 32;
   u32x4 q[KS], ka[KS], va[2][DB];
   for (int i = 0; i < KS; ++i) {
@@ -219,7 +219,7 @@ int main() {
     }
   // the attention instruction mix: din still holds the random bf16 operands of the last pass;
   // refill per type so that fp16 runs see fp16 bit patterns
-  double mix[2][2], valu_only[2];  // [bf16][D = 64, 128]
+  double mix[2][3], valu_only[2];  // [bf16][D = 64, 128, 32]
   {
     const int mix_iters = 3000;
     const float c = 0.18033688f;  // log2(e) / 8
@@ -239,17 +239,21 @@ int main() {
         }
       }
       CK(hipMemcpy(din, h.data(), h.size() * 2, hipMemcpyHostToDevice));
-      for (int which = 0; which < 3; ++which) {   // D = 64, D = 128, vector work only (D = 64)
+      for (int which = 0; which < 4; ++which) {   // D = 64, D = 128, vector work only (D = 64), D = 32
+        double best = 0.0;
+        for (int wpe = 2; wpe <= (which == 1 ? 2 : 4); ++wpe) {   // wavefronts per SIMD: the best of 2, 3, 4 (head_dim 128: its registers allow 2)
         auto launch = [&] {
-          const dim3 g(2 * cus), b(256);
+          const dim3 g(wpe * cus), b(256);
           if (bf) {
             if (which == 0) mix_loop<true, 64, true><<<g, b>>>(din, dout, mix_iters, c);
             else if (which == 1) mix_loop<true, 128, true><<<g, b>>>(din, dout, mix_iters, c);
-            else mix_loop<true, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+            else if (which == 2) mix_loop<true, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+            else mix_loop<true, 32, true><<<g, b>>>(din, dout, mix_iters, c);
           } else {
             if (which == 0) mix_loop<false, 64, true><<<g, b>>>(din, dout, mix_iters, c);
             else if (which == 1) mix_loop<false, 128, true><<<g, b>>>(din, dout, mix_iters, c);
-            else mix_loop<false, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+            else if (which == 2) mix_loop<false, 64, false><<<g, b>>>(din, dout, mix_iters, c);
+            else mix_loop<false, 32, true><<<g, b>>>(din, dout, mix_iters, c);
           }
         };
         launch();
@@ -260,11 +264,13 @@ int main() {
         CK(hipEventSynchronize(e1));
         float ms;
         CK(hipEventElapsedTime(&ms, e0, e1));
-        const double units = 2.0 * mix_iters * (2.0 * cus) * 4 * reps;   // per wavefront 2 units per iteration
-        const double flops = units * 4.0 * (which == 1 ? 128 : 64) * 32 * 32;
+        const double units = 2.0 * mix_iters * ((double)wpe * cus) * 4 * reps;   // per wavefront 2 units per iteration
+        const double flops = units * 4.0 * (which == 1 ? 128 : (which == 3 ? 32 : 64)) * 32 * 32;
         const double t = flops / (ms * 1e-3) / 1e12;
-        if (which == 2) valu_only[bf] = t;
-        else mix[bf][which] = t;
+        best = t > best ? t : best;
+        }
+        if (which == 2) valu_only[bf] = best;
+        else mix[bf][which == 3 ? 2 : which] = best;
       }
     }
   }
@@ -286,9 +292,10 @@ int main() {
   printf("{\"compute_units\": %d, \"mfma_f16_zero_tflops\": %.1f, \"mfma_f16_random_tflops\": %.1f, "
          "\"mfma_bf16_zero_tflops\": %.1f, \"mfma_bf16_random_tflops\": %.1f, "
          "\"mix_f16_d64_tflops\": %.1f, \"mix_f16_d128_tflops\": %.1f, \"mix_bf16_d64_tflops\": %.1f, "
-         "\"mix_bf16_d128_tflops\": %.1f, \"softmax_valu_only_f16_d64_tflops\": %.1f, "
+         "\"mix_bf16_d128_tflops\": %.1f, \"mix_f16_d32_tflops\": %.1f, \"mix_bf16_d32_tflops\": %.1f, "
+         "\"softmax_valu_only_f16_d64_tflops\": %.1f, "
          "\"softmax_valu_only_bf16_d64_tflops\": %.1f, \"copy_gbs\": %.1f}\n",
-         cus, tf[0][0], tf[0][1], tf[1][0], tf[1][1], mix[0][0], mix[0][1], mix[1][0], mix[1][1], valu_only[0],
+         cus, tf[0][0], tf[0][1], tf[1][0], tf[1][1], mix[0][0], mix[0][1], mix[1][0], mix[1][1], mix[0][2], mix[1][2], valu_only[0],
          valu_only[1], copy_gbs);
   CK(hipFree(src));
   CK(hipFree(dst));

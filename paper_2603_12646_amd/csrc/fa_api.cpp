@@ -144,8 +144,8 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
   if (!output_rows_disjoint(a.os, p->batch, p->heads, p->max_len, p->head_dim)) return FA_ERR_BAD_SHAPE;
 
-  // head_dim 32 and 128 run the 128-row kernel only (the tile-size hint is ignored there)
-  // ... and so does a key bias unless it can ride on the pipelined global kernel
+  // head_dim 128 runs 128-row kernels only (the tile-size hint is ignored there), and so does a key
+  // bias unless it can ride on the pipelined global kernel
   const bool windowed = p->window_left >= 0 || p->window_right >= 0;
   const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
   int bm = 128;
@@ -161,6 +161,13 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
     if (t_bm == FA_TUNE_BM_MIXED && plain && mixed_fits(*p)) bm = 0;
     if (!plain && bm == 0) bm = 128;
     if (!plain && bm == 512) bm = 256;
+  } else if (p->head_dim == 32 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR) {
+    // head_dim 32 global layers: the pipelined kernel in its 128- and 256-row shapes
+    bm = choose_bm(*p);
+    if (t_bm == FA_TUNE_BM_128) bm = 128;
+    if (t_bm == FA_TUNE_BM_256) bm = 256;
+    if (bm == 0) bm = 128;
+    if (bm == 512) bm = 256;
   }
   // Key-split kernel (32 query rows per workgroup, the wavefronts split the keys): global
   // layers of head_dim 64 without a bias whose 32-row blocks number at most one per compute

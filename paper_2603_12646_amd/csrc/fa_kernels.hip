@@ -1567,7 +1567,7 @@ struct GlobalLds {
 template <class T, int D, int NQB, int NW, bool BIAS, bool ROTATE = true>
 __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoord& tc, uint16_t* lds_k,
                                             uint16_t* lds_v, float* lds_bias) {
-  static_assert(D == 64 || D == 128, "pipelined kernel: head_dim 64 or 128");
+  static_assert(D == 32 || D == 64 || D == 128, "pipelined kernel: head_dim 32, 64 or 128");
   static_assert(NW == 4 || NW == 8 || NW == 12, "4, 8 or 12 wavefronts");
   constexpr int THREADS = NW * 64;
   constexpr int BM = NW * 32 * NQB;
@@ -1633,21 +1633,37 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
   // their contents unused.
   // With 8 or 12 wavefronts, wavefronts 0..7 move one half each: wavefront w rows
   // 8 (w % 4) .. + 7 of half w / 4; the others move nothing.
-  constexpr int CH = D / 8, RPI = 64 / CH, NI = 8 / RPI;
+  // head_dim 32 (64-byte rows): a load is 16 rows, a half two loads, and wavefront w moves half
+  // w of the four (K first, K second, V first, V second) by itself.
+  constexpr int CH = D / 8, RPI = 64 / CH, NI = D == 32 ? 2 : 8 / RPI;
+  static_assert(D != 32 || NW == 4, "head_dim 32: four wavefronts");
   const int fw = wave & 3;  // row group within a half
-  uint32_t koff[NI], voff[NI];  // bytes
+  uint32_t koff[NI], voff[NI];  // bytes (head_dim 32: koff holds the wavefront's own half's offsets)
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int dl_r = 8 * fw + i * RPI + lane / CH;  // row within a 32-row half
-    koff[i] = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane % CH) ^ k_swz_d<D>(dl_r)) * 8));
-    voff[i] = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane % CH) ^ v_swz_d<D>(dl_r)) * 8));
+    if (D == 32) {
+      const int dl_r = 16 * i + lane / CH;
+      const bool is_k = wave < 2;  // wavefront-uniform
+      koff[i] = 2u * (uint32_t)(dl_r * (is_k ? a.ks[2] : a.vs[2]) +
+                                (((lane % CH) ^ (is_k ? k_swz_d<D>(dl_r) : v_swz_d<D>(dl_r))) * 8));
+      voff[i] = 0;
+    } else {
+      const int dl_r = 8 * fw + i * RPI + lane / CH;  // row within a 32-row half
+      koff[i] = 2u * (uint32_t)(dl_r * a.ks[2] + (((lane % CH) ^ k_swz_d<D>(dl_r)) * 8));
+      voff[i] = 2u * (uint32_t)(dl_r * a.vs[2] + (((lane % CH) ^ v_swz_d<D>(dl_r)) * 8));
+    }
   }
   // the four 32-row halves of a tile: global row bases kg / vg, LDS halves kdst / vdst
   auto fetch_halves = [&](const uint16_t* kga, const uint16_t* kgb, const uint16_t* vga, const uint16_t* vgb,
                           uint16_t* kstage, uint16_t* vstage) {
     uint16_t* kdst = kstage + 8 * fw * D;
     uint16_t* vdst = vstage + 8 * fw * D;
-    if (NW == 4) {
+    if (D == 32) {
+      const uint16_t* g = wave == 0 ? kga : (wave == 1 ? kgb : (wave == 2 ? vga : vgb));
+      uint16_t* dst = (wave < 2 ? kstage : vstage) + (wave & 1) * 32 * D;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) load16_to_lds(g, koff[i], dst + i * 16 * D);
+    } else if (NW == 4) {
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
         load16_to_lds(kga, koff[i], kdst + i * RPI * D);
@@ -2101,8 +2117,10 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
     else kern = fa_fwd_masked_kernel<T, 128, 1, true, true>;
   } else if (a.head_dim == 128 && global && v_path == 0) {
     kern = fa_fwd_global_kernel<T, 128, 1, 4>;
+  } else if (a.head_dim == 32 && global && v_path == 0) {
+    kern = bm == 256 ? fa_fwd_global_kernel<T, 32, 2, 4> : fa_fwd_global_kernel<T, 32, 1, 4>;
   } else if (a.head_dim != kD) {
-    // head_dim 32 global layers, and wide or one-sided windows of head_dim 32 / 128: the masked
+    // wide or one-sided windows of head_dim 32 / 128 (and the 16-bit V-read path): the masked
     // kernel covers every mask; bm is 128 here
     if (a.head_dim == 32) kern = v_path == 0 ? fa_fwd_masked_kernel<T, 32, 1, true> : fa_fwd_masked_kernel<T, 32, 1, false>;
     else kern = v_path == 0 ? fa_fwd_masked_kernel<T, 128, 1, true> : fa_fwd_masked_kernel<T, 128, 1, false>;
