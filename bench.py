@@ -375,6 +375,54 @@ def co_location_time(reps=30):
     return out
 
 
+def rotary_time(names=("c3_8k", "c5a_32k_global", "c5b_32k_local"), reps=30):
+    """The same launches with the rotary position embedding of q and k done inside the call (the
+    paper's encoder uses rotary embeddings, Sec. 2.4): ms per call with and without the rotation.
+    Angles: base 160000 on global layers, 10000 on local ones, no rescaling (the paper gives no
+    constants; the cost does not depend on them)."""
+    import torch
+    import paper_2603_12646_amd as fa
+    from workloads import ALL_CONFIGS, make_inputs
+
+    out = {}
+    for name in names:
+        w = ALL_CONFIGS[name]
+        lens, q, k, v = make_inputs(w)
+        tdt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+        qd, kd, vd = (torch.from_numpy(x).to(tdt).cuda() for x in (q, k, v))
+        o = torch.empty_like(qd)
+        lse = torch.empty((w.batch, w.heads, w.max_len), dtype=torch.float32, device="cuda")
+        sl = torch.from_numpy(np.asarray(lens, dtype=np.int32)).cuda()
+        half = w.head_dim // 2
+        inv_freq = (160000.0 if w.window < 0 else 10000.0) ** (-2.0 * np.arange(half) / w.head_dim)
+        ang = np.arange(w.max_len)[:, None] * inv_freq[None, :]
+        cos = torch.from_numpy(np.cos(ang).astype(np.float32)).cuda()
+        sin = torch.from_numpy(np.sin(ang).astype(np.float32)).cuda()
+        L, R = window_lr(w.window)
+        dt = fa.FA_DTYPE_F16 if w.dtype == "fp16" else fa.FA_DTYPE_BF16
+        res = {}
+        for label, tables in (("ms_plain", (None, None)), ("ms_with_rotation", (cos, sin))):
+            def call():
+                fa.fa_fwd_ex(dtype=dt, q=qd, k=kd, v=vd, o=o, lse=lse, seq_lens=sl, batch=w.batch, heads=w.heads,
+                             max_len=w.max_len, head_dim=w.head_dim, scale=w.scale, window_left=L, window_right=R,
+                             rope_cos=tables[0], rope_sin=tables[1])
+            t_pre = time.perf_counter()
+            while (time.perf_counter() - t_pre) * 1e3 < PRECONDITION_MS:     # as in gpu_time
+                for _ in range(8):
+                    call()
+                torch.cuda.synchronize()
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record()
+            for _ in range(reps):
+                call()
+            stop.record()
+            torch.cuda.synchronize()
+            res[label] = round(start.elapsed_time(stop) / reps, 4)
+        out[name] = res
+        del qd, kd, vd, o, lse, cos, sin
+    return out
+
+
 def measured_ceilings():
     """What this machine sustains with nothing but matrix-core instructions (zero and random
     operands) and with a plain copy: the program built from csrc/ceilings.hip, run as a child
@@ -576,6 +624,7 @@ def main():
         out["config"]["three_sessions_16k"] = {"three_streams_ms": conc_ms, "one_batched_call_ms": batch_ms}
         out["config"]["concurrent_requests_512"] = concurrent_requests_time()
         out["config"]["co_location_8k_ms_by_compute_units"] = co_location_time()
+        out["config"]["rotary_embedding_in_call"] = rotary_time()
 
     print(json.dumps(out))
 

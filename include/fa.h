@@ -61,7 +61,7 @@
 extern "C" {
 #endif
 
-#define FA_VERSION 201 /* major*10000 + minor*100 + patch */
+#define FA_VERSION 300 /* major*10000 + minor*100 + patch */
 
 enum {
   FA_OK = 0,
@@ -149,6 +149,21 @@ typedef struct fa_params {
      and scale == 0 take the general (masked) kernel. */
   const void* key_bias;
   int64_t key_bias_stride; /* elements between batch rows; 0 = max_len; >= max_len */
+  /* Rotary position embedding of q and k inside the call (the paper's classifier uses rotary
+     embeddings with a long-context frequency rescaling, Sec. 2.4; it gives neither formula nor
+     constants, so the published definition is followed and the caller supplies the angles).
+     rope_cos / rope_sin: DEVICE pointers to fp32 tables [max_len][rope_stride], entry [i][f] =
+     cos / sin of the angle of token position i and frequency f < head_dim/2 (times any amplitude
+     factor); both NULL = no rotation.  Row i of q and of k is rotated in pairs (f, f + head_dim/2):
+         x'[f] = x[f] cos[i][f] - x[f + D/2] sin[i][f],  x'[f + D/2] = x[f + D/2] cos[i][f] + x[f] sin[i][f]
+     in fp32 and rounded to the 16-bit storage type before the score product, exactly as if the
+     caller had rotated the tensors itself; v is not rotated.  Tables are shared by all batch
+     elements and heads.  16-byte alignment; rope_stride in floats, 0 = head_dim/2, else a
+     multiple of 4 and >= head_dim/2.  The 32-row key-split shape and the 384 / 512-row and mixed
+     shapes are not used with a rotation. */
+  const float* rope_cos;
+  const float* rope_sin;
+  int64_t rope_stride;
 } fa_params;
 
 /* tuning word: bits 0-3 query rows per workgroup, bits 4-7 V-operand path,

@@ -61,6 +61,9 @@ class FaParams(ctypes.Structure):
         ("tuning", ctypes.c_uint32),
         ("key_bias", ctypes.c_void_p),
         ("key_bias_stride", ctypes.c_int64),
+        ("rope_cos", ctypes.c_void_p),
+        ("rope_sin", ctypes.c_void_p),
+        ("rope_stride", ctypes.c_int64),
     ]
 
 
@@ -156,7 +159,7 @@ def fa_fwd_bf16(q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scal
 def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_len, head_dim=64,
               scale, window_left=-1, window_right=-1, q_strides=None, k_strides=None,
               v_strides=None, o_strides=None, stream=None, tuning=0, key_bias=None,
-              key_bias_stride=0, check=True):
+              key_bias_stride=0, rope_cos=None, rope_sin=None, rope_stride=0, check=True):
     """Fill an fa_params struct and call fa_fwd_ex."""
     p = FaParams()
     p.struct_size = ctypes.sizeof(FaParams)
@@ -174,4 +177,5 @@ def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_l
     p.stream = _stream(stream)
     p.tuning = tuning
     p.key_bias, p.key_bias_stride = _ptr(key_bias), key_bias_stride
+    p.rope_cos, p.rope_sin, p.rope_stride = _ptr(rope_cos), _ptr(rope_sin), rope_stride
     return _check(load_library().fa_fwd_ex(ctypes.byref(p)), check)

@@ -130,6 +130,11 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->key_bias && (reinterpret_cast<uintptr_t>(p->key_bias) & 1u)) return FA_ERR_MISALIGNED;
   if (p->key_bias_stride < 0 || (p->key_bias && p->key_bias_stride != 0 && p->key_bias_stride < p->max_len))
     return FA_ERR_BAD_SHAPE;
+  if ((p->rope_cos == nullptr) != (p->rope_sin == nullptr)) return FA_ERR_NULL_POINTER;
+  if (p->rope_cos && (!aligned16(p->rope_cos) || !aligned16(p->rope_sin) || p->rope_stride % 4 != 0))
+    return FA_ERR_MISALIGNED;
+  if (p->rope_stride < 0 || (p->rope_cos && p->rope_stride != 0 && p->rope_stride < p->head_dim / 2))
+    return FA_ERR_BAD_SHAPE;
   if (p->tuning & ~0x1337u) return FA_ERR_BAD_TUNING;  // bits of the four fields
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
   if (t_bm > FA_TUNE_BM_MIXED || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
@@ -152,7 +157,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (p->head_dim == 64 && !bias_on_masked_kernel) {
     // 384 (12 wavefronts x 32 rows), 512 (8 wavefronts x 64 rows) and the mixed launch exist for
     // global layers without a key bias on the transpose-read path only
-    const bool plain = !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR;
+    const bool plain = !windowed && !p->key_bias && !p->rope_cos && t_v != FA_TUNE_V_SCALAR;
     bm = choose_bm(*p);
     if (t_bm == FA_TUNE_BM_128) bm = 128;
     if (t_bm == FA_TUNE_BM_256) bm = 256;
@@ -177,7 +182,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   // no difference.  Its lanes address rows by 32-bit byte offsets from the (batch, head) slice.
   {
     const int64_t row_stride = a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2];
-    const bool eligible = p->head_dim == 64 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR &&
+    const bool eligible = p->head_dim == 64 && !windowed && !p->key_bias && !p->rope_cos && t_v != FA_TUNE_V_SCALAR &&
                           (double)p->max_len * (double)row_stride * 2.0 < 4.0e9;
     const int64_t blocks32 = (((int64_t)p->max_len + 31) / 32) * p->batch * p->heads;
     if (eligible && (t_bm == FA_TUNE_BM_32 || (t_bm == FA_TUNE_BM_AUTO && blocks32 <= 256 && p->max_len > 128)))
@@ -195,6 +200,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   a.key_bias = p->key_bias;
   a.kb_stride = p->key_bias_stride ? p->key_bias_stride : p->max_len;
   a.inv_abs_scale = p->scale != 0.0f ? 1.0f / std::fabs(p->scale) : 0.0f;
+  a.rope_cos = p->rope_cos;
+  a.rope_sin = p->rope_sin;
+  a.rope_stride = p->rope_stride ? p->rope_stride : p->head_dim / 2;
   const float c = std::fabs(p->scale) * kLog2e;
   a.c = c;
   a.negate_q = std::signbit(p->scale) && p->scale != 0.0f ? 1 : 0;

@@ -12,6 +12,9 @@ struct FaKernelArgs {
   const void* key_bias;     // device, [batch][kb_stride] 16-bit values, may be null
   int64_t kb_stride;        // elements between batch rows of key_bias
   float inv_abs_scale;      // 1 / |scale| (0 when scale is 0): key bias in raw-score units
+  const float* rope_cos;    // device, [max_len][rope_stride] fp32 tables, or null: q and k are rotated
+  const float* rope_sin;    // by position (pairs (f, f + head_dim/2)) and rounded to 16 bits first
+  int64_t rope_stride;      // floats between table rows (>= head_dim / 2, multiple of 4)
   int32_t batch, heads, max_len;
   int32_t head_dim;         // 32, 64 or 128
   int64_t qs[3], ks[3], vs[3], os[3];  // element strides: batch, head, row

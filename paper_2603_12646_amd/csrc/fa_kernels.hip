@@ -536,7 +536,62 @@ __device__ __forceinline__ void zero_fill(const FaKernelArgs& a, const TileCoord
     for (int row = tc.q0 + tid; row < tc.q0 + BM && row < N; row += THREADS) lsep[row] = -INFINITY;
 }
 
-template <class T, int NQB, int KS>
+// ---- rotary position embedding (optional) ----------------------------------------------
+// Eight pairs (lo[e], hi[e]) = elements (f + e, f + e + head_dim/2) of one row are rotated by
+// the row's angles: lo' = lo cos - hi sin, hi' = hi cos + lo sin, in fp32, and rounded to the
+// storage type (nearest even).  cs / sn point at the row's table entries f .. f + 7.
+template <class T>
+__device__ __forceinline__ void rotate8(uint4& lo, uint4& hi, const float* cs, const float* sn) {
+  const float4 c0 = *(const float4*)cs, c1 = *(const float4*)(cs + 4);
+  const float4 s0 = *(const float4*)sn, s1 = *(const float4*)(sn + 4);
+  const float cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+  const float ss[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+  const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+  uint32_t lo_out[4], hi_out[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    float l[2], h[2], lr[2], hr[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      l[x] = T::to_float((uint16_t)(lw[w] >> (16 * x)));
+      h[x] = T::to_float((uint16_t)(hw[w] >> (16 * x)));
+      lr[x] = __builtin_fmaf(l[x], cc[2 * w + x], -(h[x] * ss[2 * w + x]));
+      hr[x] = __builtin_fmaf(h[x], cc[2 * w + x], l[x] * ss[2 * w + x]);
+    }
+    lo_out[w] = T::pack2(lr[0], lr[1]);
+    hi_out[w] = T::pack2(hr[0], hr[1]);
+  }
+  lo = make_uint4(lo_out[0], lo_out[1], lo_out[2], lo_out[3]);
+  hi = make_uint4(hi_out[0], hi_out[1], hi_out[2], hi_out[3]);
+}
+
+// Rotates `rows` rows of K in place in LDS (all threads of the workgroup take part; the caller
+// puts barriers around the call).  Element e of tile row r lives at
+// tile[r * stride + (((e / 8) ^ swizzle(r & 31)) * 8) + e % 8], swizzle = k_swz_d<D> for tiles
+// written by direct loads (SWIZZLED) and 0 for padded tiles; tile row r is key key0 + r
+// (clamped into the tensor: rows outside it are never used unmasked).
+template <class T, int D, bool SWIZZLED>
+__device__ __forceinline__ void rope_rows_in_lds(const FaKernelArgs& a, uint16_t* tile, int stride, int rows, int key0,
+                                                 int tid, int nthreads, int key32 = -1) {
+  // key32 >= 0: tile rows 32 .. 63 are keys key32 .. key32 + 31 instead of key0 + 32 ... (the
+  // two 32-row halves of a pipeline stage are fetched from separately clamped row bases)
+  constexpr int HALF = D / 16;  // 16-byte chunks per half row
+  for (int u = tid; u < rows * HALF; u += nthreads) {
+    const int r = u / HALF, c = u % HALF;
+    int key = (key32 >= 0 && r >= 32) ? key32 + r - 32 : key0 + r;
+    key = key < 0 ? 0 : (key < a.max_len ? key : a.max_len - 1);
+    const int sw = SWIZZLED ? k_swz_d<D>(r & 31) : 0;
+    uint4* plo = (uint4*)&tile[r * stride + ((c ^ sw) * 8)];
+    uint4* phi = (uint4*)&tile[r * stride + (((c + HALF) ^ sw) * 8)];
+    uint4 lo = *plo, hi = *phi;
+    rotate8<T>(lo, hi, a.rope_cos + (int64_t)key * a.rope_stride + 8 * c, a.rope_sin + (int64_t)key * a.rope_stride + 8 * c);
+    *plo = lo;
+    *phi = hi;
+  }
+}
+
+// ROPE = false: the kernel is never launched with a rotation (no code for it).
+template <class T, int NQB, int KS, bool ROPE = true>
 __device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp, int qw0, int lane,
                                        typename T::v8 (&qreg)[NQB][KS]) {
   const int l32 = lane & 31, hh = lane >> 5, N = a.max_len;
@@ -545,13 +600,23 @@ __device__ __forceinline__ void load_q(const FaKernelArgs& a, const uint16_t* qp
     int row = qw0 + qb * 32 + l32;
     row = row < N ? row : N - 1;
     const uint16_t* src = qp + row * a.qs[2] + hh * 8;
+    uint4 u[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) u[ks] = *(const uint4*)(src + ks * 16);
+    if (ROPE && a.rope_cos) {
+      // the lane holds columns 16 ks + 8 hh + e: chunk ks pairs with chunk ks + KS/2
+#pragma unroll
+      for (int ks = 0; ks < KS / 2; ++ks) {
+        const int64_t t = (int64_t)row * a.rope_stride + 16 * ks + 8 * hh;
+        rotate8<T>(u[ks], u[ks + KS / 2], a.rope_cos + t, a.rope_sin + t);
+      }
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      uint4 u = *(const uint4*)(src + ks * 16);
       if (a.negate_q) {
-        u.x ^= 0x80008000u; u.y ^= 0x80008000u; u.z ^= 0x80008000u; u.w ^= 0x80008000u;
+        u[ks].x ^= 0x80008000u; u[ks].y ^= 0x80008000u; u[ks].z ^= 0x80008000u; u[ks].w ^= 0x80008000u;
       }
-      qreg[qb][ks] = as_v8<T>(u);
+      qreg[qb][ks] = as_v8<T>(u[ks]);
     }
   }
 }
@@ -789,6 +854,11 @@ __global__ __launch_bounds__(kThreads, ((D == 128 && !BIAS) || NQB == 2) ? 2 : 1
   fetch(t_lo);
   stash(0);
   __syncthreads();
+  // rotary embedding: a staged K tile is rotated in place before anybody reads it
+  if (a.rope_cos) {
+    rope_rows_in_lds<T, D, false>(a, lds_k[0], SK, kBN, t_lo * kBN, tid, kThreads);
+    __syncthreads();
+  }
 
   int buf = 0;
   for (int t = t_lo; t < t_hi; ++t) {
@@ -809,6 +879,10 @@ __global__ __launch_bounds__(kThreads, ((D == 128 && !BIAS) || NQB == 2) ? 2 : 1
     if (t + 1 < t_hi) stash(buf ^ 1);
     __syncthreads();
     buf ^= 1;
+    if (a.rope_cos && t + 1 < t_hi) {
+      rope_rows_in_lds<T, D, false>(a, lds_k[buf], SK, kBN, (t + 1) * kBN, tid, kThreads);
+      __syncthreads();
+    }
   }
   // the loop ended with a barrier: the K stages are free
   epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, &lds_k[0][0] + wave * epi_patch(D));
@@ -894,7 +968,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_kernel(const FaKern
   const int qw_last = (qw0 + 32 < n ? qw0 + 32 : n) - 1;  // < qw0: all padding
   const bool wave_has_rows = qw_last >= qw0;
   typename T::v8 qreg[1][4];
-  load_q<T, 1>(a, qp, qw0, lane, qreg);
+  load_q<T, 1, 4, false>(a, qp, qw0, lane, qreg);
   RowState<1> st;
   init_state(st);
   int jlo[1], jhi[1];
@@ -1027,7 +1101,7 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_window_resident_kernel(con
 
   const int qw0 = q0 + wave * 32;
   typename T::v8 qreg[1][4];
-  load_q<T, 1>(a, qp, qw0, lane, qreg);
+  load_q<T, 1, 4, false>(a, qp, qw0, lane, qreg);
 
   // only now the sequence length
   const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
@@ -1237,6 +1311,11 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
   // ---- phase 1: scores of every visible block
   wait_direct_loads();
   __syncthreads();
+  if (a.rope_cos) {
+    // rotary embedding: the K blocks are rotated in place, once for the four wavefronts
+    rope_rows_in_lds<T, D, true>(a, lds, D, (b_hi - b_lo) * 32, b_lo * 32, tid, kThreads);
+    __syncthreads();
+  }
   floatx16 sc[kTwoPhaseBlocks];
 #pragma unroll
   for (int i = 0; i < kTwoPhaseBlocks; ++i) {
@@ -1386,7 +1465,7 @@ __global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKe
     if (i < issued) issue_block(i);
 
   typename T::v8 qreg[1][4];
-  load_q<T, 1>(a, qp, q0, lane, qreg);  // every wavefront holds the same 32 query rows
+  load_q<T, 1, 4, false>(a, qp, q0, lane, qreg);  // every wavefront holds the same 32 query rows
 
   // only now the sequence length
   const int n = tc.n < 0 ? 0 : (tc.n > N ? N : tc.n);
@@ -1564,7 +1643,9 @@ struct GlobalLds {
 };
 
 // tc: the workgroup's tile (tc.n already clamped into [0, max_len]).
-template <class T, int D, int NQB, int NW, bool BIAS, bool ROTATE = true>
+// ROPE: q and k are rotated by position (a.rope_cos / a.rope_sin are set): a compile-time
+// variant, so that the kernels without a rotation carry none of its code in their loops.
+template <class T, int D, int NQB, int NW, bool BIAS, bool ROTATE = true, bool ROPE = false>
 __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoord& tc, uint16_t* lds_k,
                                             uint16_t* lds_v, float* lds_bias) {
   static_assert(D == 32 || D == 64 || D == 128, "pipelined kernel: head_dim 32, 64 or 128");
@@ -1603,7 +1684,7 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
   const bool wave_has_rows = qw_last >= qw0;
 
   typename T::v8 qreg[NQB][KS];
-  load_q<T, NQB>(a, qp, qw0, lane, qreg);
+  load_q<T, NQB, KS, ROPE>(a, qp, qw0, lane, qreg);
   RowState<NQB, D> st;
   init_state(st);
 
@@ -1776,6 +1857,13 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
     }
     wait_direct_loads();
     __syncthreads();
+    if (ROPE) {
+      // rotary embedding: every K stage is rotated in place once it has landed (stage 1 holds
+      // keys 0..31 in its second half, stage 0 keys 32..63 and min(64, N - 32) ...)
+      rope_rows_in_lds<T, D, true>(a, &lds_k[kBN * D + 32 * D], D, 32, 0, tid, THREADS);
+      rope_rows_in_lds<T, D, true>(a, lds_k, D, 64, 32, tid, THREADS, kBN > N - 32 ? N - 32 : kBN);
+      __syncthreads();
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) sA[r] = 0.f;
     if (BIAS) {
@@ -1905,6 +1993,11 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
       if (BIAS && wave == 0 && t + 1 < nf) lds_bias[(STAGE ^ 1) * kBN + lane] = bst;
       wait_direct_loads();  // this wavefront's share of the next tile has landed
       __syncthreads();
+      if (ROPE && t + 1 < nf) {
+        rope_rows_in_lds<T, D, true>(a, &lds_k[(STAGE ^ 1) * kBN * D], D, 64, (t + 1) * kBN + 32, tid, THREADS,
+                                     t + 2 == nf ? k1_last_row : (t + 1) * kBN + 64);
+        __syncthreads();
+      }
     };
     int t = 0;
     for (; t + 1 < nf; t += 2) {
@@ -1940,6 +2033,10 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
     }
   }
   __syncthreads();
+  if (ROPE && tail > 0) {
+    rope_rows_in_lds<T, D, false>(a, lds_k, SK, 64, nf * kBN, tid, THREADS);
+    __syncthreads();
+  }
   if (wave_has_rows) {
     if (nf > 0) {
       // after an even number of units the pending probabilities sit in pA; they belong
@@ -1972,7 +2069,7 @@ __device__ __forceinline__ void global_body(const FaKernelArgs& a, const TileCoo
   epilogue<T, NQB>(a, st, op, lsep, qw0, n, lane, lds_k + wave * epi_patch(D));
 }
 
-template <class T, int D, int NQB, int NW, bool BIAS = false>
+template <class T, int D, int NQB, int NW, bool BIAS = false, bool ROPE = false>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel(const FaKernelArgs a) {
   typedef GlobalLds<D, NW> L;
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[L::kKElems];
@@ -1980,7 +2077,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel
   __shared__ __attribute__((aligned(16))) float lds_bias[BIAS ? 2 * kBN : 4];  // [stage][tile row], bias / |scale|
   TileCoord tc;
   if (!locate_tile<NW * 32 * NQB>(a, tc)) return;
-  global_body<T, D, NQB, NW, BIAS>(a, tc, lds_k, lds_v, lds_bias);
+  global_body<T, D, NQB, NW, BIAS, true, ROPE>(a, tc, lds_k, lds_v, lds_bias);
 }
 
 // ======================================================================================
@@ -2094,6 +2191,9 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
   const int win_blocks = (a.wl >= 0 && a.wr >= 0) ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
   // 32-key blocks the 32 queries of one wavefront can see (they start at a multiple of 32)
   const int wave_blocks = (a.wl >= 0 && a.wr >= 0) ? (31 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+  // rotary embedding is applied by the two-phase window kernel, the pipelined global kernel
+  // (four-wavefront shapes) and the masked kernel
+  const bool rope = a.rope_cos != nullptr;
   Kernel kern = nullptr;
   unsigned threads = kThreads;
   if (!a.key_bias && !global && v_path == 0 && bm == 128 && slice_fits_32bit && win_blocks <= kResBlocks &&
@@ -2101,11 +2201,11 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
     // local layer with a narrow two-sided window (the paper's 63/64), any head_dim
     kern = a.head_dim == 32 ? fa_fwd_window_twophase_kernel<T, 32>
                             : (a.head_dim == 64 ? fa_fwd_window_twophase_kernel<T, 64> : fa_fwd_window_twophase_kernel<T, 128>);
-  } else if (a.key_bias && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
+  } else if (a.key_bias && !rope && !global && v_path == 0 && a.c > 0.f && a.head_dim == kD && bm == 128 && slice_fits_32bit &&
       win_blocks <= kResBlocks) {
     // additive key bias on a local layer whose key range stays resident in LDS
     kern = fa_fwd_window_resident_kernel<T, true>;
-  } else if (a.key_bias && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
+  } else if (a.key_bias && !rope && global && v_path == 0 && a.c > 0.f && (a.head_dim == 64 || a.head_dim == 128)) {
     // additive key bias on a global layer: the pipelined kernel with the bias as MFMA C operand
     if (a.head_dim == 128) kern = fa_fwd_global_kernel<T, 128, 1, 4, true>;
     else if (bm == 256) kern = fa_fwd_global_kernel<T, 64, 2, 4, true>;
@@ -2115,6 +2215,11 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
     if (a.head_dim == 32) kern = fa_fwd_masked_kernel<T, 32, 1, true, true>;
     else if (a.head_dim == 64) kern = fa_fwd_masked_kernel<T, 64, 1, true, true>;
     else kern = fa_fwd_masked_kernel<T, 128, 1, true, true>;
+  } else if (rope && global && v_path == 0) {
+    // rotation on a global layer: the pipelined kernel's four-wavefront shapes
+    if (a.head_dim == 128) kern = fa_fwd_global_kernel<T, 128, 1, 4, false, true>;
+    else if (a.head_dim == 32) kern = bm == 256 ? fa_fwd_global_kernel<T, 32, 2, 4, false, true> : fa_fwd_global_kernel<T, 32, 1, 4, false, true>;
+    else kern = bm == 256 ? fa_fwd_global_kernel<T, 64, 2, 4, false, true> : fa_fwd_global_kernel<T, 64, 1, 4, false, true>;
   } else if (a.head_dim == 128 && global && v_path == 0) {
     kern = fa_fwd_global_kernel<T, 128, 1, 4>;
   } else if (a.head_dim == 32 && global && v_path == 0) {
@@ -2141,7 +2246,7 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
     } else {
       kern = fa_fwd_global_kernel<T, 64, 1, 4>;
     }
-  } else if (!global && v_path == 0 && bm == 128 && slice_fits_32bit) {
+  } else if (!global && !rope && v_path == 0 && bm == 128 && slice_fits_32bit) {
     kern = win_blocks <= kResBlocks ? fa_fwd_window_resident_kernel<T> : fa_fwd_window_kernel<T>;
   } else if (bm == 256) {
     kern = v_path == 0 ? fa_fwd_masked_kernel<T, 64, 2, true> : fa_fwd_masked_kernel<T, 64, 2, false>;

@@ -95,6 +95,12 @@ def test_ex_entry_point_rejects_bad_arguments():
     assert fa.fa_fwd_ex(**{**base, "key_bias": P + 1}) == -6
     assert fa.fa_fwd_ex(**{**base, "key_bias": P, "key_bias_stride": 4}) == -2     # shorter than max_len
     assert fa.fa_fwd_ex(**{**base, "key_bias_stride": -8}) == -2
+    # rotation tables: both or neither, 16-byte aligned, rows of at least head_dim / 2 floats in fours
+    assert fa.fa_fwd_ex(**{**base, "rope_cos": P}) == -1 and fa.fa_fwd_ex(**{**base, "rope_sin": P}) == -1
+    assert fa.fa_fwd_ex(**{**base, "rope_cos": P + 4, "rope_sin": P}) == -6
+    assert fa.fa_fwd_ex(**{**base, "rope_cos": P, "rope_sin": P, "rope_stride": 34}) == -6
+    assert fa.fa_fwd_ex(**{**base, "rope_cos": P, "rope_sin": P, "rope_stride": 16}) == -2
+    assert fa.fa_fwd_ex(**{**base, "rope_stride": -4}) == -2
     assert fa.load_library().fa_fwd_ex(None) == -1
     with pytest.raises(fa.FaError) as e:
         fa.fa_fwd_ex(**{**base, "head_dim": 48, "check": True})
