@@ -170,7 +170,8 @@ typedef struct fa_params {
    bits 8-11 workgroup-to-tile mapping, bits 12-15 window kernel. */
 #define FA_TUNE_BM_AUTO 0x0u
 #define FA_TUNE_BM_128 0x1u  /* 4 wavefronts x 32 query rows  */
-#define FA_TUNE_BM_256 0x2u  /* 4 wavefronts x 64 query rows (head_dim 64 only; ignored otherwise) */
+#define FA_TUNE_BM_256 0x2u  /* head_dim 64 and 32: 4 wavefronts x 64 query rows; head_dim 128 global
+                                layers: 8 wavefronts x 32 rows on one pair of K/V stages */
 #define FA_TUNE_BM_32 0x3u   /* 32 query rows, the 4 wavefronts split the keys (global layers of
                                 head_dim 64 without a key bias; ignored otherwise).  The library
                                 picks it by itself when the call has at most 256 blocks of 32 query

@@ -123,6 +123,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if (!p->q || !p->k || !p->v || !p->o) return FA_ERR_NULL_POINTER;
   if (p->batch <= 0 || p->heads <= 0 || p->max_len <= 0) return FA_ERR_BAD_SHAPE;
   if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128) return FA_ERR_BAD_HEAD_DIM;
+  // the element count must stay inside int64 (before any stride arithmetic is done with it)
+  if ((long double)p->batch * p->heads * p->max_len * p->head_dim > 9.0e18L || p->max_len > (1 << 30))
+    return FA_ERR_BAD_SHAPE;
   if (!std::isfinite(p->scale)) return FA_ERR_BAD_SCALE;
   if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->o))
     return FA_ERR_MISALIGNED;
@@ -166,6 +169,15 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
     if (t_bm == FA_TUNE_BM_MIXED && plain && mixed_fits(*p)) bm = 0;
     if (!plain && bm == 0) bm = 128;
     if (!plain && bm == 512) bm = 256;
+  } else if (p->head_dim == 128 && !windowed && !p->key_bias && !p->rope_cos && t_v != FA_TUNE_V_SCALAR) {
+    // head_dim 128 global layers: 128 rows on four wavefronts (two workgroups per unit), or 256
+    // rows on eight wavefronts sharing one pair of K/V stages (one per unit; 2-3 % faster where
+    // its coarser tiles fill the units as well: 8K x 8 heads, 32K x 8 heads)
+    const int64_t bh = (int64_t)p->batch * p->heads;
+    const int64_t w128 = (((int64_t)p->max_len + 127) / 128) * bh, w256 = (((int64_t)p->max_len + 255) / 256) * bh;
+    bm = shape_cost(w256, 1, 8, 1.0) < shape_cost(w128, 2, 4, 1.03) ? 256 : 128;
+    if (t_bm == FA_TUNE_BM_128) bm = 128;
+    if (t_bm == FA_TUNE_BM_256) bm = 256;
   } else if (p->head_dim == 32 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR) {
     // head_dim 32 global layers: the pipelined kernel in its 128- and 256-row shapes
     bm = choose_bm(*p);
@@ -191,9 +203,8 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   const int tile_rows = bm == 0 ? 128 : bm;   // (the mixed launch sizes its own grid)
   const int64_t n_qtiles = ((int64_t)p->max_len + tile_rows - 1) / tile_rows;
   const int64_t total = n_qtiles * p->batch * p->heads;
-  // element count and grid must stay inside what the kernels index with
-  const long double elems = (long double)p->batch * p->heads * p->max_len * p->head_dim;
-  if (elems > 9.0e18L || total > 0x7FFFFFF0LL || p->max_len > (1 << 30)) return FA_ERR_BAD_SHAPE;
+  // the grid must stay inside what the kernels index with
+  if (total > 0x7FFFFFF0LL) return FA_ERR_BAD_SHAPE;
 
   a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o; a.lse = p->lse; a.seq_lens = p->seq_lens;
   a.batch = p->batch; a.heads = p->heads; a.max_len = p->max_len; a.head_dim = p->head_dim;

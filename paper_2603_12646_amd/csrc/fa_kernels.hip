@@ -2221,7 +2221,12 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
     else if (a.head_dim == 32) kern = bm == 256 ? fa_fwd_global_kernel<T, 32, 2, 4, false, true> : fa_fwd_global_kernel<T, 32, 1, 4, false, true>;
     else kern = bm == 256 ? fa_fwd_global_kernel<T, 64, 2, 4, false, true> : fa_fwd_global_kernel<T, 64, 1, 4, false, true>;
   } else if (a.head_dim == 128 && global && v_path == 0) {
-    kern = fa_fwd_global_kernel<T, 128, 1, 4>;
+    if (bm == 256) {
+      kern = fa_fwd_global_kernel<T, 128, 1, 8>;   // eight wavefronts on one pair of K/V stages
+      threads = 512;
+    } else {
+      kern = fa_fwd_global_kernel<T, 128, 1, 4>;
+    }
   } else if (a.head_dim == 32 && global && v_path == 0) {
     kern = bm == 256 ? fa_fwd_global_kernel<T, 32, 2, 4> : fa_fwd_global_kernel<T, 32, 1, 4>;
   } else if (a.head_dim != kD) {

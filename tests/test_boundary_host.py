@@ -2,6 +2,7 @@
 the header declares, and rejects bad arguments before touching a device."""
 import ctypes
 import math
+import os
 import pathlib
 import re
 
@@ -184,3 +185,90 @@ def test_header_is_plain_c_and_its_struct_layout_is_the_bindings(tmp_path):
     assert int(out[6]) < 0 and int(out[7]) < 0      # null pointers: rejected on the host
     assert int(out[8]) == 0
     assert out[9].strip() == fa.fa_strerror(0)
+
+
+SANITIZER_DRIVER = r"""
+// Host side of the boundary under AddressSanitizer / UBSan: fa_api.cpp compiled by the host
+// compiler against stub launchers (no HIP, no device), driven through rejections and through
+// calls that reach the launcher with every tile shape and stride form.
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+#include "fa.h"
+#include "fa_args.h"
+
+static FaKernelArgs last;
+static int last_bm = -7, launches = 0;
+int fa_launch_f16(const FaKernelArgs& a, int bm, int, int, void*) { last = a; last_bm = bm; ++launches; return 0; }
+int fa_launch_bf16(const FaKernelArgs& a, int bm, int, int, void*) { last = a; last_bm = bm; ++launches; return 0; }
+
+#define EXPECT(cond) do { if (!(cond)) { printf("FAILED line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
+
+int main() {
+  alignas(16) static char buf[64];
+  void* P = buf;
+  fa_params p;
+  std::memset(&p, 0, sizeof p);
+  p.struct_size = sizeof p;
+  p.q = p.k = p.v = P; p.o = P;
+  p.batch = 1; p.heads = 12; p.max_len = 8192; p.head_dim = 64; p.scale = 0.125f;
+  p.window_left = p.window_right = -1;
+  EXPECT(fa_fwd_ex(&p) == 0 && launches == 1 && last_bm == 0);            // one 8K sequence: the mixed launch
+  p.heads = 16; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 512);
+  p.heads = 24; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 256);
+  p.heads = 12; p.max_len = 512; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 32);
+  p.batch = 32; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 128);
+  p.batch = 1; p.max_len = 32768; p.window_left = 63; p.window_right = 64;
+  EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 128 && last.wl == 63 && last.wr == 64);
+  p.window_left = 40000; p.window_right = -1; EXPECT(fa_fwd_ex(&p) == 0 && last.wl == -1 && last.wr == -1);
+  for (int d : {32, 64, 128})
+    for (unsigned t = 0; t <= 6; ++t) {
+      p.head_dim = d; p.tuning = t; p.window_left = p.window_right = -1;
+      EXPECT(fa_fwd_ex(&p) == 0);
+      EXPECT(last.total_tiles > 0 && last.n_qtiles > 0 && last.xcd_per > 0);
+    }
+  p.tuning = 0; p.head_dim = 64;
+  // strides: [batch, len, heads, dim] passes, interleaved output rows do not
+  const int64_t bshd[3] = {(int64_t)32768 * 12 * 64, 64, 12 * 64};
+  std::memcpy(p.q_strides, bshd, sizeof bshd); std::memcpy(p.o_strides, bshd, sizeof bshd);
+  EXPECT(fa_fwd_ex(&p) == 0 && last.qs[2] == 12 * 64 && last.os[1] == 64);
+  p.o_strides[1] = 0; EXPECT(fa_fwd_ex(&p) == FA_ERR_BAD_SHAPE);
+  std::memset(p.o_strides, 0, sizeof p.o_strides);
+  // extremes: sizes that overflow a grid or an int64 element count are refused, not wrapped
+  p.batch = 1 << 30; p.heads = 1 << 30; p.max_len = 1 << 30; EXPECT(fa_fwd_ex(&p) == FA_ERR_BAD_SHAPE);
+  p.batch = 1; p.heads = 1; p.max_len = (1 << 30) + 1; EXPECT(fa_fwd_ex(&p) == FA_ERR_BAD_SHAPE);
+  p.max_len = 1; EXPECT(fa_fwd_ex(&p) == 0);
+  p.scale = 0.0f; EXPECT(fa_fwd_ex(&p) == 0 && last.tau_raw > 1e30f);
+  p.scale = -3.0f; EXPECT(fa_fwd_ex(&p) == 0 && last.negate_q == 1 && last.c > 0.f);
+  // the plain entry points and the queries
+  EXPECT(fa_fwd(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 128, nullptr) == 0 && last.wl == 63 && last.wr == 64);
+  EXPECT(fa_fwd_bf16(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 0, nullptr) == FA_ERR_BAD_WINDOW);
+  EXPECT(fa_workspace_bytes(4, 12, 32768, 64) == 0);
+  for (int code = -12; code <= 3; ++code) EXPECT(std::strlen(fa_strerror(code)) > 0);
+  printf("ok %d launches\n", launches);
+  return 0;
+}
+"""
+
+
+def test_host_boundary_under_address_and_undefined_sanitizers(tmp_path):
+    """fa_api.cpp built by g++ with -fsanitize=address,undefined against stub launchers: the
+    validation, stride, overflow and tile-shape arithmetic runs clean, and the kernel-shape
+    choices reach the launcher as documented."""
+    import shutil
+    import subprocess
+
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    src = tmp_path / "driver.cpp"
+    src.write_text(SANITIZER_DRIVER)
+    exe = tmp_path / "driver"
+    csrc = ROOT / "paper_2603_12646_amd" / "csrc"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-I", str(ROOT / "include"), "-I", str(csrc), str(src), str(csrc / "fa_api.cpp"), "-o", str(exe)],
+                   check=True)
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.startswith("ok ") and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
