@@ -500,6 +500,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 256 MiB three times, so a rocprofv3 "
                          "--pmc run of this command has a kernel of known traffic to scale against")
+    ap.add_argument("--precondition-ms", type=float, default=PRECONDITION_MS,
+                    help="untimed calls of the workload for this long before the warm-up calls "
+                         "(0 for short profiler runs that should hold few dispatches)")
     ap.add_argument("--tuning", type=lambda x: int(x, 0), default=0,
                     help="FA_TUNE_* bits forwarded to fa_fwd_ex (sweeps); 0 = library's choice")
     args = ap.parse_args()
@@ -521,7 +524,7 @@ def main():
     w = ALL_CONFIGS[args.workload]
     lens, q, k, v = make_inputs(w)
     flops, nbytes = algorithmic_work(w, lens)
-    wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup, args.tuning)
+    wall_ms, ev_ms = gpu_time(w, lens, q, k, v, args.steps, args.warmup, args.tuning, args.precondition_ms)
     # the reported rate is taken from the HIP-event time of the timed region (the host's wall
     # clock around the same region, which adds the final synchronisation, is reported beside it)
     tflops = flops / (ev_ms * 1e-3) / 1e12
@@ -549,7 +552,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "max_len": w.max_len,
                    "head_dim": w.head_dim, "seq_lens": [int(x) for x in lens][:8], "window": w.window,
                    "scale": w.scale, "qk_gain": w.qk_gain, "tuning": args.tuning,
-                   "preconditioning_ms": PRECONDITION_MS},
+                   "preconditioning_ms": args.precondition_ms},
         "roofline": roof,
     }
 

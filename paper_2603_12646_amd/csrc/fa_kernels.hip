@@ -1262,21 +1262,40 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
   // 32-bit byte offset from the slice.
   constexpr int CH = D / 8, RPL = 64 / CH, LPB = 32 / RPL;   // D = 32: 4, 16, 2;  64: 8, 8, 4;  128: 16, 4, 8
   constexpr int kLoadsPerWave = kResBlocks * LPB / kWaves;
-  auto request_blocks = [&](const uint16_t* base, uint32_t row_bytes, bool is_k) {
+  const bool all_rows_exist = b_hi_ld * 32 <= N;   // workgroup-uniform
+  auto request_blocks = [&](const uint16_t* base, int64_t row_elems, bool is_k) {
+    const uint32_t row_bytes = 2u * (uint32_t)row_elems;
+    if (all_rows_exist) {
+      // no clamp needed: a load's per-lane offset depends on its part only (LPB / kWaves or one
+      // distinct value per wavefront), the block advances the scalar base
+      const uint16_t* blk_base = base + (int64_t)b_lo * 32 * row_elems;
 #pragma unroll
-    for (int x = 0; x < kLoadsPerWave; ++x) {
-      const int j = wave + kWaves * x;          // wavefront-uniform
-      const int i = j / LPB, part = j % LPB;
-      if (b_lo + i < b_hi_ld) {
-        const int r = part * RPL + lane / CH;   // row within the block
-        const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
-        const int jg = (b_lo + i) * 32 + r;
-        const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
-        load16_to_lds(base, jc * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8), &lds[i * kBlk + part * RPL * D]);
+      for (int x = 0; x < kLoadsPerWave; ++x) {
+        const int j = wave + kWaves * x;          // wavefront-uniform
+        const int i = j / LPB, part = j % LPB;
+        if (b_lo + i < b_hi_ld) {
+          const int r = part * RPL + lane / CH;   // row within the block
+          const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
+          load16_to_lds(blk_base + (int64_t)i * 32 * row_elems, (uint32_t)r * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8),
+                        &lds[i * kBlk + part * RPL * D]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < kLoadsPerWave; ++x) {
+        const int j = wave + kWaves * x;
+        const int i = j / LPB, part = j % LPB;
+        if (b_lo + i < b_hi_ld) {
+          const int r = part * RPL + lane / CH;
+          const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
+          const int jg = (b_lo + i) * 32 + r;
+          const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
+          load16_to_lds(base, jc * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8), &lds[i * kBlk + part * RPL * D]);
+        }
       }
     }
   };
-  request_blocks(kp, 2u * (uint32_t)a.ks[2], true);
+  request_blocks(kp, a.ks[2], true);
 
   const int qw0 = q0 + wave * 32;
   typename T::v8 qreg[1][KS];
@@ -1316,12 +1335,12 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
     rope_rows_in_lds<T, D, true>(a, lds, D, (b_hi - b_lo) * 32, b_lo * 32, tid, kThreads);
     __syncthreads();
   }
-  floatx16 sc[kTwoPhaseBlocks];
+  floatx16 sc[kTwoPhaseBlocks];   // sc[i] is set and used for i < cnt only
 #pragma unroll
   for (int i = 0; i < kTwoPhaseBlocks; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
     if (i < cnt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[i][r] = 0.f;
       const uint16_t* kblk = &lds[(fb + i - b_lo) * kBlk];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) sc[i] = T::mfma(load_k_frag_swz_d<T, D>(kblk, l32, hh, ks), qreg[0][ks], sc[i]);
@@ -1330,7 +1349,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
   __syncthreads();  // every wavefront has its K fragments out of the region
 
   // ---- phase 2: request V into the same region; softmax meanwhile
-  request_blocks(vp, 2u * (uint32_t)a.vs[2], false);
+  request_blocks(vp, a.vs[2], false);
   uint32_t vis[kTwoPhaseBlocks];
   float t0 = -INFINITY;
 #pragma unroll
@@ -1340,9 +1359,15 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
       const int kb0 = (fb + i) * 32;
       // blocks every valid query of the wavefront sees completely need no mask work
       const bool interior = kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr;
-      vis[i] = interior ? 0xFFFFu : visible_bits(kb0, hh, jlo, jhi);
+      if (interior) {
+        vis[i] = 0xFFFFu;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis[i] >> r & 1) ? sc[i][r] : -INFINITY);
+        for (int r = 0; r < 16; r += 2) t0 = fmaxf(fmaxf(t0, sc[i][r]), sc[i][r + 1]);
+      } else {
+        vis[i] = visible_bits(kb0, hh, jlo, jhi);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis[i] >> r & 1) ? sc[i][r] : -INFINITY);
+      }
     }
   }
   RowState<1, D> st;
