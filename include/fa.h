@@ -194,6 +194,9 @@ typedef struct fa_params {
                                          LDS region; four workgroups per compute unit), i.e. the
                                          pipelined kernels with K and V resident or in a ring */
 
+#define FA_TUNE_WIN_TWO_PHASE 0x2000u /* local layers: the two-phase kernel wherever it applies (narrow two-sided
+                                         windows), also on calls small enough to be latency-bound */
+
 int fa_fwd_ex(const fa_params* params);
 
 /*

@@ -16,7 +16,7 @@ __all__ = [
     "FaParams", "FaError", "load_library", "LIB_PATH",
     "FA_DTYPE_F16", "FA_DTYPE_BF16",
     "FA_TUNE_BM_128", "FA_TUNE_BM_256", "FA_TUNE_BM_32", "FA_TUNE_BM_384", "FA_TUNE_BM_512", "FA_TUNE_BM_MIXED", "FA_TUNE_V_LDS_TRANSPOSE", "FA_TUNE_V_SCALAR",
-    "FA_TUNE_MAP_LINEAR", "FA_TUNE_MAP_XCD", "FA_TUNE_WIN_PIPELINED",
+    "FA_TUNE_MAP_LINEAR", "FA_TUNE_MAP_XCD", "FA_TUNE_WIN_PIPELINED", "FA_TUNE_WIN_TWO_PHASE",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -27,7 +27,7 @@ FA_TUNE_BM_128, FA_TUNE_BM_256, FA_TUNE_BM_32 = 0x1, 0x2, 0x3
 FA_TUNE_BM_384, FA_TUNE_BM_512, FA_TUNE_BM_MIXED = 0x4, 0x5, 0x6
 FA_TUNE_V_LDS_TRANSPOSE, FA_TUNE_V_SCALAR = 0x10, 0x20
 FA_TUNE_MAP_LINEAR, FA_TUNE_MAP_XCD = 0x100, 0x200
-FA_TUNE_WIN_PIPELINED = 0x1000
+FA_TUNE_WIN_PIPELINED, FA_TUNE_WIN_TWO_PHASE = 0x1000, 0x2000
 
 
 class FaError(RuntimeError):

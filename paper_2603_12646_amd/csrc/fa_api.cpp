@@ -138,7 +138,7 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
     return FA_ERR_MISALIGNED;
   if (p->rope_stride < 0 || (p->rope_cos && p->rope_stride != 0 && p->rope_stride < p->head_dim / 2))
     return FA_ERR_BAD_SHAPE;
-  if (p->tuning & ~0x1337u) return FA_ERR_BAD_TUNING;  // bits of the four fields
+  if (p->tuning & ~0x3337u) return FA_ERR_BAD_TUNING;  // bits of the four fields
   const unsigned t_bm = p->tuning & 0xFu, t_v = p->tuning & 0xF0u, t_map = p->tuning & 0xF00u;
   if (t_bm > FA_TUNE_BM_MIXED || t_v > FA_TUNE_V_SCALAR || t_map > FA_TUNE_MAP_XCD)
     return FA_ERR_BAD_TUNING;
@@ -233,7 +233,9 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   a.xcd_per = (int32_t)per;
   const int v_path = t_v == FA_TUNE_V_SCALAR ? 1 : 0;
 
-  const int win_kernel = (p->tuning & FA_TUNE_WIN_PIPELINED) ? 1 : 0;
+  const unsigned t_win = p->tuning & 0xF000u;
+  if (t_win > FA_TUNE_WIN_TWO_PHASE) return FA_ERR_BAD_TUNING;
+  const int win_kernel = t_win == FA_TUNE_WIN_PIPELINED ? 1 : (t_win == FA_TUNE_WIN_TWO_PHASE ? 2 : 0);
   return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, win_kernel, p->stream)
                                   : fa_launch_bf16(a, bm, v_path, win_kernel, p->stream);
 }

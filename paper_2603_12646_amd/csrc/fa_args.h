@@ -33,6 +33,7 @@ struct FaKernelArgs {
 // bm: query rows per workgroup: 32 (key-split kernel), 128, 256, 384 (12 wavefronts), 512 (8
 // wavefronts), or 0 = 256-row and 128-row workgroups mixed (one sequence of at most 768 tiles of 128 rows over all heads); v_path: 0 = LDS
 // transpose reads, 1 = 16-bit reads.
-// win_kernel: 0 = library's choice among the window kernels, 1 = never the two-phase kernel.
+// win_kernel: 0 = library's choice among the window kernels, 1 = never the two-phase kernel, 2 = the
+// two-phase kernel wherever it applies.
 int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream);
 int fa_launch_bf16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream);

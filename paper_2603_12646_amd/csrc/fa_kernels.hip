@@ -2216,13 +2216,19 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
   const int win_blocks = (a.wl >= 0 && a.wr >= 0) ? (127 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
   // 32-key blocks the 32 queries of one wavefront can see (they start at a multiple of 32)
   const int wave_blocks = (a.wl >= 0 && a.wr >= 0) ? (31 + a.wr) / 32 + (a.wl + 31) / 32 + 1 : 1 << 30;
+  Kernel kern = nullptr;
+  unsigned threads = kThreads;
   // rotary embedding is applied by the two-phase window kernel, the pipelined global kernel
   // (four-wavefront shapes) and the masked kernel
   const bool rope = a.rope_cos != nullptr;
-  Kernel kern = nullptr;
-  unsigned threads = kThreads;
+  // Calls of at most 1.5 tiles per compute unit are bound by one workgroup's latency, not by
+  // bandwidth: there the pipelined kernel with K and V resident (ONE memory round trip per
+  // workgroup instead of two) is as fast or a little faster (measured, 12 heads: 2K tokens 7.4
+  // against 7.8 us, 4K equal, 8K 17.3 against 14.9 us, 32K 43 against 37 us); it exists for
+  // head_dim 64 only.
+  const bool latency_bound = a.head_dim == kD && a.total_tiles <= 384;
   if (!a.key_bias && !global && v_path == 0 && bm == 128 && slice_fits_32bit && win_blocks <= kResBlocks &&
-      wave_blocks <= kTwoPhaseBlocks && win_kernel != 1) {
+      wave_blocks <= kTwoPhaseBlocks && win_kernel != 1 && !(latency_bound && !rope && win_kernel != 2)) {
     // local layer with a narrow two-sided window (the paper's 63/64), any head_dim
     kern = a.head_dim == 32 ? fa_fwd_window_twophase_kernel<T, 32>
                             : (a.head_dim == 64 ? fa_fwd_window_twophase_kernel<T, 64> : fa_fwd_window_twophase_kernel<T, 128>);

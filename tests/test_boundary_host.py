@@ -83,7 +83,7 @@ def test_ex_entry_point_rejects_bad_arguments():
     base = dict(dtype=fa.FA_DTYPE_F16, q=P, k=P, v=P, o=P, batch=1, heads=1, max_len=8, scale=1.0,
                 stream=0, check=False)
     assert fa.fa_fwd_ex(**{**base, "dtype": 7}) == -7
-    assert fa.fa_fwd_ex(**{**base, "tuning": 0x4000}) == -9
+    assert fa.fa_fwd_ex(**{**base, "tuning": 0x4000}) == -9 and fa.fa_fwd_ex(**{**base, "tuning": 0x3000}) == -9
     assert fa.fa_fwd_ex(**{**base, "tuning": 0x7}) == -9 and fa.fa_fwd_ex(**{**base, "tuning": 0x8}) == -9
     # output rows that would overlap: zero / negative batch or head stride, rows inside each other
     two = {**base, "batch": 2, "heads": 2}

@@ -29,7 +29,8 @@ TUNINGS = {
     "bm384_linear": fa.FA_TUNE_BM_384 | fa.FA_TUNE_MAP_LINEAR,
     "bm512_xcd": fa.FA_TUNE_BM_512 | fa.FA_TUNE_MAP_XCD,
     "win_pipelined": fa.FA_TUNE_WIN_PIPELINED,
-    "win_pipelined_linear": fa.FA_TUNE_WIN_PIPELINED | fa.FA_TUNE_MAP_LINEAR,
+    "win_two_phase": fa.FA_TUNE_WIN_TWO_PHASE,
+    "win_two_phase_linear": fa.FA_TUNE_WIN_TWO_PHASE | fa.FA_TUNE_MAP_LINEAR,
     "mixed_linear": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_LINEAR,
     "mixed_xcd": fa.FA_TUNE_BM_MIXED | fa.FA_TUNE_MAP_XCD,
 }
@@ -81,6 +82,40 @@ def test_seq_lens_degenerate_values(dtype, kern):
         o_ref, lse_ref = attention_oracle(q, k, v, lens, 0.125, L, R)
         o, lse = run_simple(q, k, v, lens, dtype, 0.125, window, tuning=GLOBAL_KERNELS[kern])
         check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"w={window} {kern}")
+
+
+WINDOW_KERNELS = {"pipelined": fa.FA_TUNE_WIN_PIPELINED, "two_phase": fa.FA_TUNE_WIN_TWO_PHASE}
+
+
+@pytest.mark.parametrize("kern", sorted(WINDOW_KERNELS))
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("D", [32, 64, 128])
+def test_window_kernels_tile_edges_degenerate_lengths_and_garbage_padding(D, dtype, kern):
+    """Both families of window kernels (small calls take the pipelined ones by themselves) on the
+    paper's 63/64 window and two narrower ones: lengths around tile edges, degenerate sequence
+    lengths, and NaN / inf in the padded rows (valid rows must not change by a bit)."""
+    tun = WINDOW_KERNELS[kern]
+    scale = 1.0 / np.sqrt(D)
+    for N in (1, 31, 33, 64, 65, 127, 129, 257, 640):
+        _, q, k, v = draw(250 + N, 1, 2, N, D, dtype)
+        for left, right in ((63, 64), (0, 0), (31, 32)):
+            o_ref, lse_ref = attention_oracle(q, k, v, None, scale, left, right)
+            o, lse = run_ex(q, k, v, None, dtype, scale, left, right, tuning=tun)
+            check_against(o, lse, o_ref, lse_ref, None, dtype, relative=True, label=f"N={N} ({left},{right}) D{D} {kern}")
+    B, H, N = 6, 2, 192
+    _, q, k, v = draw(350, B, H, N, D, dtype)
+    lens = [0, -5, 1000, 1, 128, 191]
+    o_ref, lse_ref = attention_oracle(q, k, v, lens, scale, 63, 64)
+    o, lse = run_ex(q, k, v, lens, dtype, scale, 63, 64, tuning=tun)
+    check_against(o, lse, o_ref, lse_ref, lens, dtype, relative=True, label=f"degenerate D{D} {kern}")
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for b, n in enumerate(lens):
+        n = min(max(n, 0), N)
+        q2[b, :, n:] = np.inf
+        k2[b, :, n:] = np.nan
+        v2[b, :, n:] = -np.inf
+    o2, lse2 = run_ex(q2, k2, v2, lens, dtype, scale, 63, 64, tuning=tun)
+    assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
 
 
 @pytest.mark.parametrize("kern", sorted(GLOBAL_KERNELS))
@@ -327,7 +362,8 @@ def test_valid_call_returns_zero_and_bad_call_leaves_output_untouched():
 
 # ------------------------------------------------------------------ head_dim 32 and 128
 HD_TUNINGS = {"auto": 0, "scalar_linear": fa.FA_TUNE_V_SCALAR | fa.FA_TUNE_MAP_LINEAR,
-              "bm256_where_it_exists": fa.FA_TUNE_BM_256, "win_pipelined": fa.FA_TUNE_WIN_PIPELINED}
+              "bm256_where_it_exists": fa.FA_TUNE_BM_256, "win_pipelined": fa.FA_TUNE_WIN_PIPELINED,
+              "win_two_phase": fa.FA_TUNE_WIN_TWO_PHASE}
 
 
 @pytest.mark.parametrize("tuning", sorted(HD_TUNINGS))
