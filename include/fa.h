@@ -20,7 +20,8 @@
  * Q, K, V and a 1-D padding description, attributes scale, window_size_left,
  * window_size_right, execution on the caller's HIP stream, run-time dispatch on
  * head_dim 32 / 64 / 128).  fa_fwd and fa_fwd_bf16 describe the padding by sequence
- * lengths; fa_fwd_ex also accepts the operator's additive 1-D key bias (Eq. 1).
+ * lengths; fa_fwd_ex also accepts the operator's additive 1-D key bias (Eq. 1) and
+ * can apply the model's rotary position embedding to q and k inside the call (Sec. 2.4).
  * Every call can be recorded into a HIP graph.
  *
  * Memory and layout

@@ -712,7 +712,8 @@ def sample_rows(n, rng, count):
     return np.array(sorted(edge | set(rest)), dtype=np.int64)
 
 
-@pytest.mark.parametrize("name", ["c3_8k", "c4_16k_x3", "c5a_32k_global", "c5b_32k_local", "d128_8k", "d128_32k"])
+@pytest.mark.parametrize("name", ["c3_8k", "c4_16k_x3", "c5a_32k_global", "c5b_32k_local", "d128_8k", "d128_32k",
+                                  "d128_32k_local", "d32_8k", "d32_32k", "d32_32k_local"])
 def test_named_large_configs_sampled_rows(name):
     """Full-size launch, as bench.py times it; the oracle recomputes sampled query
     rows (the first and last 130 valid rows of every (batch, head) plus random ones)
