@@ -401,11 +401,16 @@ def rotary_time(names=("c3_8k", "c5a_32k_global", "c5b_32k_local"), reps=30):
         L, R = window_lr(w.window)
         dt = fa.FA_DTYPE_F16 if w.dtype == "fp16" else fa.FA_DTYPE_BF16
         res = {}
-        for label, tables in (("ms_plain", (None, None)), ("ms_with_rotation", (cos, sin))):
+        need = fa.fa_rope_scratch_bytes(w.batch, w.heads, w.max_len, w.head_dim)
+        scratch = torch.empty(need, dtype=torch.uint8, device="cuda") if w.window < 0 else None
+        legs = [("ms_plain", (None, None), None), ("ms_with_rotation", (cos, sin), None)]
+        if scratch is not None:     # global layer: q and k rotated once ahead of the call, in lent scratch
+            legs.append(("ms_with_rotation_ahead_in_lent_scratch", (cos, sin), scratch))
+        for label, tables, scr in legs:
             def call():
                 fa.fa_fwd_ex(dtype=dt, q=qd, k=kd, v=vd, o=o, lse=lse, seq_lens=sl, batch=w.batch, heads=w.heads,
                              max_len=w.max_len, head_dim=w.head_dim, scale=w.scale, window_left=L, window_right=R,
-                             rope_cos=tables[0], rope_sin=tables[1])
+                             rope_cos=tables[0], rope_sin=tables[1], scratch=scr, scratch_bytes=need if scr is not None else 0)
             t_pre = time.perf_counter()
             while (time.perf_counter() - t_pre) * 1e3 < PRECONDITION_MS:     # as in gpu_time
                 for _ in range(8):
@@ -419,7 +424,7 @@ def rotary_time(names=("c3_8k", "c5a_32k_global", "c5b_32k_local"), reps=30):
             torch.cuda.synchronize()
             res[label] = round(start.elapsed_time(stop) / reps, 4)
         out[name] = res
-        del qd, kd, vd, o, lse, cos, sin
+        del qd, kd, vd, o, lse, cos, sin, scratch
     return out
 
 

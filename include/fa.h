@@ -62,7 +62,7 @@
 extern "C" {
 #endif
 
-#define FA_VERSION 300 /* major*10000 + minor*100 + patch */
+#define FA_VERSION 301 /* major*10000 + minor*100 + patch */
 
 enum {
   FA_OK = 0,
@@ -165,6 +165,15 @@ typedef struct fa_params {
   const float* rope_cos;
   const float* rope_sin;
   int64_t rope_stride;
+  /* Optional DEVICE scratch the caller lends to the call (16-byte aligned), or NULL.  It is used in
+     one case: a rotation on a GLOBAL layer (no window).  There the in-call rotation turns every K
+     tile once per query tile; with at least fa_rope_scratch_bytes(...) of scratch a first kernel
+     rotates q and k once into the scratch and the attention kernel (in any of its tile shapes)
+     runs on the rotated copies: same bits, 8K tokens x 12 heads 0.27 -> 0.21 ms.  Too small a
+     scratch, a local layer or no rotation: ignored.  The scratch may be reused as soon as the
+     stream has passed the call; two calls that overlap in time must not share it. */
+  void* scratch;
+  size_t scratch_bytes;
 } fa_params;
 
 /* tuning word: bits 0-3 query rows per workgroup, bits 4-7 V-operand path,
@@ -206,6 +215,10 @@ int fa_fwd_ex(const fa_params* params);
  * shape: the working set is the caller's O(n) tensors only.
  */
 size_t fa_workspace_bytes(int batch, int heads, int max_len, int head_dim);
+
+/* Bytes of fa_params.scratch with which a rotation on a global layer of this shape is done ahead
+   of the attention kernel: rotated copies of q and k, 2 * batch * heads * max_len * head_dim * 2. */
+size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int head_dim);
 
 /* Static, NUL-terminated description of a return code (FA_ERR_* or 0).  Positive
    codes map to a generic "HIP runtime error" string. */

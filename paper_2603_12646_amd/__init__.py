@@ -12,7 +12,7 @@ import ctypes
 import os
 
 __all__ = [
-    "fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_workspace_bytes", "fa_strerror", "fa_version",
+    "fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_workspace_bytes", "fa_rope_scratch_bytes", "fa_strerror", "fa_version",
     "FaParams", "FaError", "load_library", "LIB_PATH",
     "FA_DTYPE_F16", "FA_DTYPE_BF16",
     "FA_TUNE_BM_128", "FA_TUNE_BM_256", "FA_TUNE_BM_32", "FA_TUNE_BM_384", "FA_TUNE_BM_512", "FA_TUNE_BM_MIXED", "FA_TUNE_V_LDS_TRANSPOSE", "FA_TUNE_V_SCALAR",
@@ -64,6 +64,8 @@ class FaParams(ctypes.Structure):
         ("rope_cos", ctypes.c_void_p),
         ("rope_sin", ctypes.c_void_p),
         ("rope_stride", ctypes.c_int64),
+        ("scratch", ctypes.c_void_p),
+        ("scratch_bytes", ctypes.c_size_t),
     ]
 
 
@@ -89,8 +91,10 @@ def load_library():
         fn.restype = ctypes.c_int
     lib.fa_fwd_ex.argtypes = [ctypes.POINTER(FaParams)]
     lib.fa_fwd_ex.restype = ctypes.c_int
-    lib.fa_workspace_bytes.argtypes = [ctypes.c_int] * 4
-    lib.fa_workspace_bytes.restype = ctypes.c_size_t
+    for name in ("fa_workspace_bytes", "fa_rope_scratch_bytes"):
+        fn = getattr(lib, name)
+        fn.argtypes = [ctypes.c_int] * 4
+        fn.restype = ctypes.c_size_t
     lib.fa_strerror.argtypes = [ctypes.c_int]
     lib.fa_strerror.restype = ctypes.c_char_p
     lib.fa_version.argtypes = []
@@ -128,6 +132,10 @@ def fa_workspace_bytes(batch: int, heads: int, max_len: int, head_dim: int) -> i
     return int(load_library().fa_workspace_bytes(batch, heads, max_len, head_dim))
 
 
+def fa_rope_scratch_bytes(batch: int, heads: int, max_len: int, head_dim: int) -> int:
+    return int(load_library().fa_rope_scratch_bytes(batch, heads, max_len, head_dim))
+
+
 def _check(rc: int, check: bool) -> int:
     if check and rc != 0:
         raise FaError(rc, fa_strerror(rc))
@@ -159,7 +167,8 @@ def fa_fwd_bf16(q, k, v, o, lse, batch, heads, seq_lens, max_len, head_dim, scal
 def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_len, head_dim=64,
               scale, window_left=-1, window_right=-1, q_strides=None, k_strides=None,
               v_strides=None, o_strides=None, stream=None, tuning=0, key_bias=None,
-              key_bias_stride=0, rope_cos=None, rope_sin=None, rope_stride=0, check=True):
+              key_bias_stride=0, rope_cos=None, rope_sin=None, rope_stride=0, scratch=None, scratch_bytes=0,
+              check=True):
     """Fill an fa_params struct and call fa_fwd_ex."""
     p = FaParams()
     p.struct_size = ctypes.sizeof(FaParams)
@@ -178,4 +187,5 @@ def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_l
     p.tuning = tuning
     p.key_bias, p.key_bias_stride = _ptr(key_bias), key_bias_stride
     p.rope_cos, p.rope_sin, p.rope_stride = _ptr(rope_cos), _ptr(rope_sin), rope_stride
+    p.scratch, p.scratch_bytes = _ptr(scratch), scratch_bytes
     return _check(load_library().fa_fwd_ex(ctypes.byref(p)), check)

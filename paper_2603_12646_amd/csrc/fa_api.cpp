@@ -116,9 +116,26 @@ int choose_bm(const fa_params& p) {
 
 }  // namespace
 
+namespace {
+// scratch / scratch_bytes: what the call may use
+int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes);
+}  // namespace
+
 extern "C" int fa_fwd_ex(const fa_params* p) {
   if (!p) return FA_ERR_NULL_POINTER;
   if (p->struct_size != sizeof(fa_params)) return FA_ERR_BAD_STRUCT;
+  return fwd_ex_impl(p, p->scratch, p->scratch_bytes);
+}
+
+extern "C" size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int head_dim) {
+  if (batch <= 0 || heads <= 0 || max_len <= 0 || head_dim <= 0) return 0;
+  return (size_t)2 * (size_t)batch * (size_t)heads * (size_t)max_len * (size_t)head_dim * 2u;
+}
+
+namespace {
+int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes) {
+  fa_params local = *p_in;
+  const fa_params* p = &local;
   if (p->dtype != FA_DTYPE_F16 && p->dtype != FA_DTYPE_BF16) return FA_ERR_BAD_DTYPE;
   if (!p->q || !p->k || !p->v || !p->o) return FA_ERR_NULL_POINTER;
   if (p->batch <= 0 || p->heads <= 0 || p->max_len <= 0) return FA_ERR_BAD_SHAPE;
@@ -151,6 +168,33 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   if ((rc = resolve_strides(p->v_strides, a.vs, p->heads, p->max_len, p->head_dim))) return rc;
   if ((rc = resolve_strides(p->o_strides, a.os, p->heads, p->max_len, p->head_dim))) return rc;
   if (!output_rows_disjoint(a.os, p->batch, p->heads, p->max_len, p->head_dim)) return FA_ERR_BAD_SHAPE;
+
+  FaRopeArgs r;
+  bool rotate_first = false;
+  // A rotation on a global layer with scratch to spare: q and k are rotated once, ahead of the
+  // attention kernel, into dense copies in the scratch; from here on the call is a plain one
+  // on those copies (every tile shape is open to it again).
+  if (p->rope_cos && p->window_left < 0 && p->window_right < 0) {
+    const size_t need = fa_rope_scratch_bytes(p->batch, p->heads, p->max_len, p->head_dim);
+    if (scratch && !aligned16(scratch)) return FA_ERR_MISALIGNED;
+    if (scratch && scratch_bytes >= need) {
+      rotate_first = true;
+      std::memset(&r, 0, sizeof(r));
+      r.q = p->q; r.k = p->k;
+      r.q_out = scratch;
+      r.k_out = static_cast<char*>(scratch) + need / 2;
+      std::memcpy(r.qs, a.qs, sizeof r.qs);
+      std::memcpy(r.ks, a.ks, sizeof r.ks);
+      r.rope_cos = p->rope_cos; r.rope_sin = p->rope_sin;
+      r.rope_stride = p->rope_stride ? p->rope_stride : p->head_dim / 2;
+      r.batch = p->batch; r.heads = p->heads; r.max_len = p->max_len; r.head_dim = p->head_dim;
+      local.q = r.q_out;   // (the rotation is enqueued below, once nothing can be refused any more)
+      local.k = r.k_out;
+      local.rope_cos = local.rope_sin = nullptr;
+      dense_strides(a.qs, p->heads, p->max_len, p->head_dim);
+      dense_strides(a.ks, p->heads, p->max_len, p->head_dim);
+    }
+  }
 
   // head_dim 128 runs 128-row kernels only (the tile-size hint is ignored there), and so does a key
   // bias unless it can ride on the pipelined global kernel
@@ -236,9 +280,14 @@ extern "C" int fa_fwd_ex(const fa_params* p) {
   const unsigned t_win = p->tuning & 0xF000u;
   if (t_win > FA_TUNE_WIN_TWO_PHASE) return FA_ERR_BAD_TUNING;
   const int win_kernel = t_win == FA_TUNE_WIN_PIPELINED ? 1 : (t_win == FA_TUNE_WIN_TWO_PHASE ? 2 : 0);
+  if (rotate_first) {
+    const int rc_rot = fa_launch_rope_rotate(r, p->dtype == FA_DTYPE_BF16, p->stream);
+    if (rc_rot != 0) return rc_rot;
+  }
   return p->dtype == FA_DTYPE_F16 ? fa_launch_f16(a, bm, v_path, win_kernel, p->stream)
                                   : fa_launch_bf16(a, bm, v_path, win_kernel, p->stream);
 }
+}  // namespace
 
 static int fwd_simple(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
                       int batch, int heads, const int32_t* seq_lens, int max_len, int head_dim,

@@ -29,6 +29,21 @@ struct FaKernelArgs {
   int32_t xcd_per;  // ceil(heads * n_qtiles / 8)
 };
 
+// Rotation of q and k ahead of a global layer (rows of both tensors rotated by position and
+// written, rounded to the storage type, to dense [batch, heads, max_len, head_dim] copies).
+struct FaRopeArgs {
+  const void* q;
+  const void* k;
+  void* q_out;
+  void* k_out;
+  int64_t qs[3], ks[3];     // element strides of the inputs: batch, head, row
+  const float* rope_cos;
+  const float* rope_sin;
+  int64_t rope_stride;
+  int32_t batch, heads, max_len, head_dim;
+};
+int fa_launch_rope_rotate(const FaRopeArgs& r, int is_bf16, void* stream);
+
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
 // bm: query rows per workgroup: 32 (key-split kernel), 128, 256, 384 (12 wavefronts), 512 (8
 // wavefronts), or 0 = 256-row and 128-row workgroups mixed (one sequence of at most 768 tiles of 128 rows over all heads); v_path: 0 = LDS

@@ -2203,6 +2203,32 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_global_mixed_kernel(const 
   }
 }
 
+// ======================================================================================
+// Rotation of q and k ahead of a global layer.  A global layer that rotates K inside the call
+// rotates every K tile once per query tile; when the caller lends scratch memory, q and k are
+// rotated once here instead (the same rotate8, the same rounding: the attention kernel then
+// sees bit for bit what the in-call rotation would have produced) and the plain kernels run on
+// the copies.  One thread rotates eight pairs of one row; blockIdx.z < batch: q, else k.
+// ======================================================================================
+template <class T>
+__global__ __launch_bounds__(256) void fa_rope_rotate_kernel(const FaRopeArgs r) {
+  const int half = r.head_dim / 16;                      // 16-byte chunks per half row: 2, 4 or 8
+  const int rows_per_block = 256 / half;
+  const int row = blockIdx.x * rows_per_block + (int)threadIdx.x / half, c = (int)threadIdx.x % half;
+  if (row >= r.max_len) return;
+  const int h = blockIdx.y;
+  const bool is_k = (int)blockIdx.z >= r.batch;
+  const int b = is_k ? (int)blockIdx.z - r.batch : (int)blockIdx.z;
+  const int64_t* st = is_k ? r.ks : r.qs;
+  const uint16_t* src = (const uint16_t*)(is_k ? r.k : r.q) + b * st[0] + h * st[1] + row * st[2];
+  uint16_t* dst = (uint16_t*)(is_k ? r.k_out : r.q_out) + (((int64_t)b * r.heads + h) * r.max_len + row) * r.head_dim;
+  uint4 lo = *(const uint4*)(src + 8 * c), hi = *(const uint4*)(src + r.head_dim / 2 + 8 * c);
+  const int64_t t = (int64_t)row * r.rope_stride + 8 * c;
+  rotate8<T>(lo, hi, r.rope_cos + t, r.rope_sin + t);
+  *(uint4*)(dst + 8 * c) = lo;
+  *(uint4*)(dst + r.head_dim / 2 + 8 * c) = hi;
+}
+
 template <class T>
 int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
   typedef void (*Kernel)(const FaKernelArgs);
@@ -2297,6 +2323,15 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
 }
 
 }  // namespace
+
+int fa_launch_rope_rotate(const FaRopeArgs& r, int is_bf16, void* stream) {
+  const int rows_per_block = 256 / (r.head_dim / 16);
+  const dim3 grid((unsigned)((r.max_len + rows_per_block - 1) / rows_per_block), (unsigned)r.heads, 2u * (unsigned)r.batch);
+  FaRopeArgs args = r;
+  void* argv[] = {&args};
+  const void* kern = is_bf16 ? (const void*)fa_rope_rotate_kernel<BF16> : (const void*)fa_rope_rotate_kernel<F16>;
+  return (int)hipLaunchKernel(kern, grid, dim3(256), argv, 0, (hipStream_t)stream);
+}
 
 int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
   return launch<F16>(a, bm, v_path, win_kernel, stream);

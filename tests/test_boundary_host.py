@@ -20,7 +20,7 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_strerror",
+    assert declared_functions() == ["fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_rope_scratch_bytes", "fa_strerror",
                                     "fa_version", "fa_workspace_bytes"]
 
 
@@ -202,6 +202,9 @@ static FaKernelArgs last;
 static int last_bm = -7, launches = 0;
 int fa_launch_f16(const FaKernelArgs& a, int bm, int, int, void*) { last = a; last_bm = bm; ++launches; return 0; }
 int fa_launch_bf16(const FaKernelArgs& a, int bm, int, int, void*) { last = a; last_bm = bm; ++launches; return 0; }
+static FaRopeArgs last_rot;
+static int rotations = 0;
+int fa_launch_rope_rotate(const FaRopeArgs& r, int, void*) { last_rot = r; ++rotations; return 0; }
 
 #define EXPECT(cond) do { if (!(cond)) { printf("FAILED line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
 
@@ -241,6 +244,24 @@ int main() {
   p.max_len = 1; EXPECT(fa_fwd_ex(&p) == 0);
   p.scale = 0.0f; EXPECT(fa_fwd_ex(&p) == 0 && last.tau_raw > 1e30f);
   p.scale = -3.0f; EXPECT(fa_fwd_ex(&p) == 0 && last.negate_q == 1 && last.c > 0.f);
+  // a rotation on a global layer: in the call without scratch, ahead of it (on dense copies) with enough
+  alignas(16) static float table[64];
+  alignas(16) static char lent[64];
+  p.batch = 1; p.heads = 12; p.max_len = 8192; p.head_dim = 64; p.scale = 0.125f; p.window_left = p.window_right = -1;
+  p.rope_cos = p.rope_sin = table;
+  EXPECT(fa_fwd_ex(&p) == 0 && rotations == 0 && last.rope_cos == table && last_bm != 0 && last.q == P);
+  p.scratch = lent; p.scratch_bytes = fa_rope_scratch_bytes(1, 12, 8192, 64) - 1;
+  EXPECT(fa_fwd_ex(&p) == 0 && rotations == 0 && last.rope_cos == table);                    // too small: ignored
+  p.scratch_bytes += 1;
+  EXPECT(fa_rope_scratch_bytes(1, 12, 8192, 64) == (size_t)2 * 12 * 8192 * 64 * 2);
+  EXPECT(fa_fwd_ex(&p) == 0 && rotations == 1 && last.rope_cos == nullptr && last.q == lent && last_bm == 0);
+  EXPECT(last_rot.q == P && last_rot.k_out == lent + 12 * 8192 * 64 * 2 && last.k == last_rot.k_out && last.ks[2] == 64);
+  p.scratch = lent + 4; EXPECT(fa_fwd_ex(&p) == FA_ERR_MISALIGNED && rotations == 1);
+  p.scratch = lent; p.window_left = 63; p.window_right = 64;
+  EXPECT(fa_fwd_ex(&p) == 0 && rotations == 1 && last.rope_cos == table);                    // local layer: in the call
+  p.window_left = p.window_right = -1; p.tuning = 0x7;
+  EXPECT(fa_fwd_ex(&p) == FA_ERR_BAD_TUNING && rotations == 1);                              // refused: nothing enqueued
+  p.tuning = 0; p.rope_cos = p.rope_sin = nullptr; p.scratch = nullptr; p.scratch_bytes = 0;
   // the plain entry points and the queries
   EXPECT(fa_fwd(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 128, nullptr) == 0 && last.wl == 63 && last.wr == 64);
   EXPECT(fa_fwd_bf16(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 0, nullptr) == FA_ERR_BAD_WINDOW);

@@ -21,7 +21,8 @@ def tables(N, D, base=10000.0, freq_scale=None, amplitude=1.0):
     return c32, s32, c32.astype(np.float64), s32.astype(np.float64)
 
 
-def run_rope(q32, k32, v32, lens, dtype, scale, c32, s32, left=-1, right=-1, tuning=0, key_bias=None, rope_stride=0):
+def run_rope(q32, k32, v32, lens, dtype, scale, c32, s32, left=-1, right=-1, tuning=0, key_bias=None, rope_stride=0,
+             scratch_bytes=0, **extra):
     B, H, N, D = q32.shape
     q, k, v = to_dev(q32, dtype), to_dev(k32, dtype), to_dev(v32, dtype)
     o = poison((B, H, N, D), dtype)
@@ -29,9 +30,11 @@ def run_rope(q32, k32, v32, lens, dtype, scale, c32, s32, left=-1, right=-1, tun
     sl = None if lens is None else torch.as_tensor(np.asarray(lens), dtype=torch.int32).cuda()
     cd, sd = torch.from_numpy(np.ascontiguousarray(c32)).cuda(), torch.from_numpy(np.ascontiguousarray(s32)).cuda()
     kb = None if key_bias is None else to_dev(np.ascontiguousarray(key_bias, dtype=np.float32), dtype)
+    # lent scratch: poisoned, so that anything read from it that the call did not write shows up
+    scratch = torch.full((scratch_bytes,), 0xFF, dtype=torch.uint8, device="cuda") if scratch_bytes else None
     fa.fa_fwd_ex(dtype=FA_DT[dtype], q=q, k=k, v=v, o=o, lse=lse, seq_lens=sl, batch=B, heads=H, max_len=N,
                  head_dim=D, scale=scale, window_left=left, window_right=right, tuning=tuning, key_bias=kb,
-                 rope_cos=cd, rope_sin=sd, rope_stride=rope_stride)
+                 rope_cos=cd, rope_sin=sd, rope_stride=rope_stride, scratch=scratch, scratch_bytes=scratch_bytes, **extra)
     torch.cuda.synchronize()
     return o.double().cpu().numpy(), lse.double().cpu().numpy()
 
@@ -134,3 +137,49 @@ def test_rope_named_workloads_sampled_rows(name):
             o_ref, lse_ref = attention_oracle_rope_rows(q, k, v, c64, s64, w.dtype, b, h, rows, n, w.scale, L, R)
             assert np.abs(o[b, h, rows] - o_ref).max() <= TOL[w.dtype]["max_abs"], (name, b, h)
             assert np.abs(lse[b, h, rows] - lse_ref).max() <= LSE_TOL, (name, b, h)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("D,B,H,N,lens", [(64, 2, 3, 700, [700, 333]), (32, 1, 2, 513, [500]), (128, 1, 2, 300, [300]),
+                                          (64, 1, 12, 8192, [7900])])
+def test_rope_rotation_ahead_of_the_call_with_lent_scratch(D, B, H, N, lens, dtype):
+    """A global layer with a rotation and enough lent scratch rotates q and k once, ahead of the
+    attention kernel: the same bits as the in-call rotation (the same rotation arithmetic and
+    rounding, and a row's attention arithmetic does not depend on the tile shape), with and
+    without a key bias, and from strided (packed) inputs; a scratch one byte short is ignored."""
+    _, q, k, v = draw(9600 + D, B, H, N, D, dtype)
+    c32, s32, c64, s64 = tables(N, D, base=160000.0)
+    scale = 1.0 / np.sqrt(D)
+    need = fa.fa_rope_scratch_bytes(B, H, N, D)
+    assert need == 2 * B * H * N * D * 2
+    # the pipelined kernel on both sides (a small plain call would take the key-split kernel, whose
+    # summation order differs); the 8K case is left to the library: mixed shapes against 128 rows
+    tun = fa.FA_TUNE_BM_128 if N <= 1024 else 0
+    o_in, lse_in = run_rope(q, k, v, lens, dtype, scale, c32, s32, tuning=tun)
+    o_sc, lse_sc = run_rope(q, k, v, lens, dtype, scale, c32, s32, tuning=tun, scratch_bytes=need)
+    assert np.array_equal(o_in, o_sc) and np.array_equal(lse_in, lse_sc)
+    o_short, lse_short = run_rope(q, k, v, lens, dtype, scale, c32, s32, tuning=tun, scratch_bytes=need - 1)
+    assert np.array_equal(o_in, o_short) and np.array_equal(lse_in, lse_short)
+    if N <= 1024:
+        o_ref, lse_ref = attention_oracle_rope(q, k, v, c64, s64, dtype, lens, scale)
+        check_against(o_sc, lse_sc, o_ref, lse_ref, lens, dtype, label=f"rope scratch D{D} {dtype}")
+        rng = np.random.default_rng(96)
+        bias = round_to_storage(rng.standard_normal((B, N)).astype(np.float32) * 0.5, dtype)
+        bias[rng.random((B, N)) < 0.1] = -np.inf
+        o_b, lse_b = run_rope(q, k, v, lens, dtype, scale, c32, s32, key_bias=bias, scratch_bytes=need)
+        o_bref, lse_bref = attention_oracle_rope(q, k, v, c64, s64, dtype, lens, scale, key_bias=bias)
+        check_against(o_b, lse_b, o_bref, lse_bref, lens, dtype, relative=True, label=f"rope scratch + bias D{D} {dtype}")
+        # packed [B, N, 3, H, D] input: q and k are strided views
+        qkv = np.stack([q.transpose(0, 2, 1, 3), k.transpose(0, 2, 1, 3), v.transpose(0, 2, 1, 3)], axis=2)   # [B, N, 3, H, D]
+        dev = to_dev(np.ascontiguousarray(qkv), dtype)
+        strides = (N * 3 * H * D, D, 3 * H * D)
+        o = poison((B, H, N, D), dtype)
+        lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+        scratch = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")
+        fa.fa_fwd_ex(dtype=FA_DT[dtype], q=dev[:, :, 0], k=dev[:, :, 1], v=dev[:, :, 2], o=o, lse=lse,
+                     seq_lens=torch.tensor(lens, dtype=torch.int32).cuda(), batch=B, heads=H, max_len=N, head_dim=D,
+                     scale=scale, q_strides=strides, k_strides=strides, v_strides=strides,
+                     rope_cos=torch.from_numpy(c32).cuda(), rope_sin=torch.from_numpy(s32).cuda(),
+                     scratch=scratch, scratch_bytes=need, tuning=tun)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.double().cpu().numpy(), o_sc) and np.array_equal(lse.double().cpu().numpy(), lse_sc)
