@@ -62,7 +62,7 @@
 extern "C" {
 #endif
 
-#define FA_VERSION 301 /* major*10000 + minor*100 + patch */
+#define FA_VERSION 400 /* major*10000 + minor*100 + patch */
 
 enum {
   FA_OK = 0,
@@ -78,7 +78,9 @@ enum {
                                 is not a multiple of 8 elements                        */
   FA_ERR_BAD_DTYPE = -7,     /* dtype is not FA_DTYPE_F16 / FA_DTYPE_BF16              */
   FA_ERR_BAD_STRUCT = -8,    /* fa_params.struct_size does not match this header       */
-  FA_ERR_BAD_TUNING = -9     /* unknown bits in fa_params.tuning                       */
+  FA_ERR_BAD_TUNING = -9,    /* unknown bits in fa_params.tuning                       */
+  FA_ERR_SCRATCH = -10       /* fa_fwd_ex_static_scratch: the call would use more scratch
+                                than FA_STATIC_SCRATCH_BYTES                           */
 };
 
 enum { FA_DTYPE_F16 = 0, FA_DTYPE_BF16 = 1 };
@@ -219,6 +221,22 @@ size_t fa_workspace_bytes(int batch, int heads, int max_len, int head_dim);
 /* Bytes of fa_params.scratch with which a rotation on a global layer of this shape is done ahead
    of the attention kernel: rotated copies of q and k, 2 * batch * heads * max_len * head_dim * 2. */
 size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int head_dim);
+
+/*
+ * fa_fwd_ex_static_scratch: fa_fwd_ex for callers that cannot allocate device memory and have
+ * no scratch of their own to lend (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc).  params->scratch / scratch_bytes are ignored; where fa_fwd_ex would
+ * use a lent scratch, this call uses an array of FA_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy from the first call
+ * on it until the process ends).  A call that would need more returns FA_ERR_SCRATCH and
+ * enqueues nothing; a call that would use no scratch behaves exactly like fa_fwd_ex.  It calls
+ * no allocating routine.  All calls on one GPU share the one array: calls that overlap in time
+ * on the same GPU (different streams, different threads) race on it; calls ordered on one
+ * stream do not.  Nothing in the array needs to start at zero: every byte a call reads it has
+ * written itself.
+ */
+#define FA_STATIC_SCRATCH_BYTES (64u << 20)
+int fa_fwd_ex_static_scratch(const fa_params* params);
 
 /* Static, NUL-terminated description of a return code (FA_ERR_* or 0).  Positive
    codes map to a generic "HIP runtime error" string. */

@@ -13,6 +13,7 @@ import os
 
 __all__ = [
     "fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_workspace_bytes", "fa_rope_scratch_bytes", "fa_strerror", "fa_version",
+    "FA_STATIC_SCRATCH_BYTES",
     "FaParams", "FaError", "load_library", "LIB_PATH",
     "FA_DTYPE_F16", "FA_DTYPE_BF16",
     "FA_TUNE_BM_128", "FA_TUNE_BM_256", "FA_TUNE_BM_32", "FA_TUNE_BM_384", "FA_TUNE_BM_512", "FA_TUNE_BM_MIXED", "FA_TUNE_V_LDS_TRANSPOSE", "FA_TUNE_V_SCALAR",
@@ -91,6 +92,8 @@ def load_library():
         fn.restype = ctypes.c_int
     lib.fa_fwd_ex.argtypes = [ctypes.POINTER(FaParams)]
     lib.fa_fwd_ex.restype = ctypes.c_int
+    lib.fa_fwd_ex_static_scratch.argtypes = [ctypes.POINTER(FaParams)]
+    lib.fa_fwd_ex_static_scratch.restype = ctypes.c_int
     for name in ("fa_workspace_bytes", "fa_rope_scratch_bytes"):
         fn = getattr(lib, name)
         fn.argtypes = [ctypes.c_int] * 4
@@ -136,6 +139,9 @@ def fa_rope_scratch_bytes(batch: int, heads: int, max_len: int, head_dim: int) -
     return int(load_library().fa_rope_scratch_bytes(batch, heads, max_len, head_dim))
 
 
+FA_STATIC_SCRATCH_BYTES = 64 << 20
+
+
 def _check(rc: int, check: bool) -> int:
     if check and rc != 0:
         raise FaError(rc, fa_strerror(rc))
@@ -168,8 +174,8 @@ def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_l
               scale, window_left=-1, window_right=-1, q_strides=None, k_strides=None,
               v_strides=None, o_strides=None, stream=None, tuning=0, key_bias=None,
               key_bias_stride=0, rope_cos=None, rope_sin=None, rope_stride=0, scratch=None, scratch_bytes=0,
-              check=True):
-    """Fill an fa_params struct and call fa_fwd_ex."""
+              static_scratch=False, check=True):
+    """Fill an fa_params struct and call fa_fwd_ex (static_scratch: fa_fwd_ex_static_scratch)."""
     p = FaParams()
     p.struct_size = ctypes.sizeof(FaParams)
     p.dtype = dtype
@@ -188,4 +194,6 @@ def fa_fwd_ex(*, dtype, q, k, v, o, lse=None, seq_lens=None, batch, heads, max_l
     p.key_bias, p.key_bias_stride = _ptr(key_bias), key_bias_stride
     p.rope_cos, p.rope_sin, p.rope_stride = _ptr(rope_cos), _ptr(rope_sin), rope_stride
     p.scratch, p.scratch_bytes = _ptr(scratch), scratch_bytes
-    return _check(load_library().fa_fwd_ex(ctypes.byref(p)), check)
+    lib = load_library()
+    fn = lib.fa_fwd_ex_static_scratch if static_scratch else lib.fa_fwd_ex
+    return _check(fn(ctypes.byref(p)), check)

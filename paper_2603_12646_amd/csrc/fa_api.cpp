@@ -117,14 +117,15 @@ int choose_bm(const fa_params& p) {
 }  // namespace
 
 namespace {
-// scratch / scratch_bytes: what the call may use
-int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes);
+// scratch / scratch_bytes: what the call may use (the caller's, or the library's static array);
+// static_limit: reject a call that would use more scratch than it has instead of falling back
+int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool static_limit);
 }  // namespace
 
 extern "C" int fa_fwd_ex(const fa_params* p) {
   if (!p) return FA_ERR_NULL_POINTER;
   if (p->struct_size != sizeof(fa_params)) return FA_ERR_BAD_STRUCT;
-  return fwd_ex_impl(p, p->scratch, p->scratch_bytes);
+  return fwd_ex_impl(p, p->scratch, p->scratch_bytes, false);
 }
 
 extern "C" size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int head_dim) {
@@ -132,8 +133,21 @@ extern "C" size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int h
   return (size_t)2 * (size_t)batch * (size_t)heads * (size_t)max_len * (size_t)head_dim * 2u;
 }
 
+extern "C" int fa_fwd_ex_static_scratch(const fa_params* p) {
+  if (!p) return FA_ERR_NULL_POINTER;
+  if (p->struct_size != sizeof(fa_params)) return FA_ERR_BAD_STRUCT;
+  // only a rotation on a global layer uses scratch: every other call never touches the array
+  const bool uses_scratch = p->rope_cos && p->window_left < 0 && p->window_right < 0;
+  void* ptr = nullptr;
+  if (uses_scratch) {
+    const int rc = fa_static_scratch(&ptr);
+    if (rc != 0) return rc;
+  }
+  return fwd_ex_impl(p, ptr, uses_scratch ? (size_t)FA_STATIC_SCRATCH_BYTES : 0, true);
+}
+
 namespace {
-int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes) {
+int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool static_limit) {
   fa_params local = *p_in;
   const fa_params* p = &local;
   if (p->dtype != FA_DTYPE_F16 && p->dtype != FA_DTYPE_BF16) return FA_ERR_BAD_DTYPE;
@@ -177,6 +191,7 @@ int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes) {
   if (p->rope_cos && p->window_left < 0 && p->window_right < 0) {
     const size_t need = fa_rope_scratch_bytes(p->batch, p->heads, p->max_len, p->head_dim);
     if (scratch && !aligned16(scratch)) return FA_ERR_MISALIGNED;
+    if (static_limit && need > scratch_bytes) return FA_ERR_SCRATCH;
     if (scratch && scratch_bytes >= need) {
       rotate_first = true;
       std::memset(&r, 0, sizeof(r));
@@ -339,6 +354,7 @@ extern "C" const char* fa_strerror(int code) {
     case FA_ERR_BAD_DTYPE: return "dtype must be FA_DTYPE_F16 or FA_DTYPE_BF16";
     case FA_ERR_BAD_STRUCT: return "fa_params.struct_size mismatch";
     case FA_ERR_BAD_TUNING: return "unknown tuning bits";
+    case FA_ERR_SCRATCH: return "the call needs more scratch than the library's static array holds";
     default: return code > 0 ? "HIP runtime error" : "unknown error code";
   }
 }

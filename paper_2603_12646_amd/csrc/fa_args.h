@@ -43,6 +43,9 @@ struct FaRopeArgs {
   int32_t batch, heads, max_len, head_dim;
 };
 int fa_launch_rope_rotate(const FaRopeArgs& r, int is_bf16, void* stream);
+// Address, on the current device, of the library's static scratch array of FA_STATIC_SCRATCH_BYTES
+// (looked up once per device).  Returns hipError_t as int.
+int fa_static_scratch(void** ptr);
 
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
 // bm: query rows per workgroup: 32 (key-split kernel), 128, 256, 384 (12 wavefronts), 512 (8

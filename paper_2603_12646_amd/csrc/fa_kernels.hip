@@ -53,8 +53,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
+#include "fa.h"
 #include "fa_args.h"
 
 namespace {
@@ -2229,6 +2231,11 @@ __global__ __launch_bounds__(256) void fa_rope_rotate_kernel(const FaRopeArgs r)
   *(uint4*)(dst + r.head_dim / 2 + 8 * c) = hi;
 }
 
+// Scratch for callers that cannot allocate (fa_fwd_ex_static_scratch): one array per GPU, held
+// until the process ends.  The name below is a host-side stand-in for the symbol; the device
+// address is looked up once per device and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char fa_static_scratch_array[FA_STATIC_SCRATCH_BYTES];
+
 template <class T>
 int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {
   typedef void (*Kernel)(const FaKernelArgs);
@@ -2331,6 +2338,25 @@ int fa_launch_rope_rotate(const FaRopeArgs& r, int is_bf16, void* stream) {
   void* argv[] = {&args};
   const void* kern = is_bf16 ? (const void*)fa_rope_rotate_kernel<BF16> : (const void*)fa_rope_rotate_kernel<F16>;
   return (int)hipLaunchKernel(kern, grid, dim3(256), argv, 0, (hipStream_t)stream);
+}
+
+int fa_static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static void* per_device[kMaxDevices] = {};   // each GPU holds its own copy of the array at its own address
+  static std::mutex lock;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(fa_static_scratch_array));
+    if (e != hipSuccess) return (int)e;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  return 0;
 }
 
 int fa_launch_f16(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stream) {

@@ -20,8 +20,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_entry_points():
-    assert declared_functions() == ["fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_rope_scratch_bytes", "fa_strerror",
-                                    "fa_version", "fa_workspace_bytes"]
+    assert declared_functions() == ["fa_fwd", "fa_fwd_bf16", "fa_fwd_ex", "fa_fwd_ex_static_scratch",
+                                    "fa_rope_scratch_bytes", "fa_strerror", "fa_version", "fa_workspace_bytes"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -41,7 +41,7 @@ def test_version_and_struct_size_match_header():
 
 def test_error_enum_values_in_header_match_strerror():
     codes = dict((name, int(val)) for name, val in re.findall(r"(FA_ERR_[A-Z_]+) = (-\d+)", HEADER))
-    assert len(codes) == 9 and sorted(codes.values()) == list(range(-9, 0))
+    assert len(codes) == 10 and sorted(codes.values()) == list(range(-10, 0))
     seen = set()
     for name, code in codes.items():
         msg = fa.fa_strerror(code)
@@ -205,6 +205,9 @@ int fa_launch_bf16(const FaKernelArgs& a, int bm, int, int, void*) { last = a; l
 static FaRopeArgs last_rot;
 static int rotations = 0;
 int fa_launch_rope_rotate(const FaRopeArgs& r, int, void*) { last_rot = r; ++rotations; return 0; }
+alignas(16) static char static_array[16];
+static int lookups = 0;
+int fa_static_scratch(void** ptr) { *ptr = static_array; ++lookups; return 0; }
 
 #define EXPECT(cond) do { if (!(cond)) { printf("FAILED line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
 
@@ -261,12 +264,24 @@ int main() {
   EXPECT(fa_fwd_ex(&p) == 0 && rotations == 1 && last.rope_cos == table);                    // local layer: in the call
   p.window_left = p.window_right = -1; p.tuning = 0x7;
   EXPECT(fa_fwd_ex(&p) == FA_ERR_BAD_TUNING && rotations == 1);                              // refused: nothing enqueued
-  p.tuning = 0; p.rope_cos = p.rope_sin = nullptr; p.scratch = nullptr; p.scratch_bytes = 0;
+  // the entry point with the library's own scratch: the array instead of the lent buffer, refusal beyond its size
+  p.tuning = 0; p.scratch = lent; p.scratch_bytes = 1u << 30;
+  EXPECT(fa_fwd_ex_static_scratch(&p) == 0 && rotations == 2 && lookups == 1 && last.q == static_array && last_rot.q_out == static_array);
+  p.max_len = 32768;
+  EXPECT(fa_rope_scratch_bytes(1, 12, 32768, 64) > FA_STATIC_SCRATCH_BYTES);
+  EXPECT(fa_fwd_ex_static_scratch(&p) == FA_ERR_SCRATCH && rotations == 2);
+  p.window_left = 63; p.window_right = 64;
+  EXPECT(fa_fwd_ex_static_scratch(&p) == 0 && rotations == 2 && lookups == 2 && last.rope_cos == table);   // local layer: no scratch used
+  p.window_left = p.window_right = -1; p.rope_cos = p.rope_sin = nullptr;
+  EXPECT(fa_fwd_ex_static_scratch(&p) == 0 && rotations == 2 && lookups == 2 && last.q == P);               // no rotation: plain call
+  EXPECT(fa_fwd_ex_static_scratch(nullptr) == FA_ERR_NULL_POINTER);
+  p.max_len = 8192; p.scratch = nullptr; p.scratch_bytes = 0;
   // the plain entry points and the queries
   EXPECT(fa_fwd(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 128, nullptr) == 0 && last.wl == 63 && last.wr == 64);
   EXPECT(fa_fwd_bf16(P, P, P, P, nullptr, 2, 3, nullptr, 100, 64, 1.0f, 0, nullptr) == FA_ERR_BAD_WINDOW);
   EXPECT(fa_workspace_bytes(4, 12, 32768, 64) == 0);
   for (int code = -12; code <= 3; ++code) EXPECT(std::strlen(fa_strerror(code)) > 0);
+  EXPECT(std::strstr(fa_strerror(FA_ERR_SCRATCH), "scratch") != nullptr);
   printf("ok %d launches\n", launches);
   return 0;
 }
