@@ -233,7 +233,8 @@ size_t fa_rope_scratch_bytes(int batch, int heads, int max_len, int head_dim);
  * no allocating routine.  All calls on one GPU share the one array: calls that overlap in time
  * on the same GPU (different streams, different threads) race on it; calls ordered on one
  * stream do not.  Nothing in the array needs to start at zero: every byte a call reads it has
- * written itself.
+ * written itself.  The first call on a GPU looks the array's address up (hipGetSymbolAddress);
+ * make that call before a capture begins if the calls are to be recorded into a HIP graph.
  */
 #define FA_STATIC_SCRATCH_BYTES (64u << 20)
 int fa_fwd_ex_static_scratch(const fa_params* params);

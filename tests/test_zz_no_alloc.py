@@ -71,3 +71,46 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit_and_ignores_what_n
     rc_s, o_s, lse_s = call(q32, k32, v32, 32768, "bf16", c32, s32, static=True, left=63, right=64)
     rc_l, o_l, lse_l = call(q32, k32, v32, 32768, "bf16", c32, s32, static=False, left=63, right=64)
     assert rc_s == 0 and rc_l == 0 and np.array_equal(o_s, o_l) and np.array_equal(lse_s, lse_l)
+
+
+def test_static_scratch_call_recorded_into_a_hip_graph_and_replayed():
+    """What the entry point is for: the rotation kernel and the attention kernel of a call that
+    lends nothing, recorded into a HIP graph (the scratch address was looked up by the eager
+    warm-up call on this GPU) and replayed with fresh inputs and eager work in between; every
+    replay must reproduce the eager fa_fwd_ex result with lent scratch bit for bit."""
+    H, N, n, D, dtype = 6, 2048, 1999, 64, "bf16"
+    cos, sin = rope_tables(N, D, base=160000.0)
+    cd, sd = torch.from_numpy(cos.astype(np.float32)).cuda(), torch.from_numpy(sin.astype(np.float32)).cuda()
+    sl = torch.tensor([n], dtype=torch.int32).cuda()
+    qd = torch.zeros((1, H, N, D), dtype=torch.bfloat16, device="cuda")
+    kd, vd = torch.zeros_like(qd), torch.zeros_like(qd)
+    o = poison((1, H, N, D), dtype)
+    lse = torch.zeros((1, H, N), dtype=torch.float32, device="cuda")
+    need = fa.fa_rope_scratch_bytes(1, H, N, D)
+    lent = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+    def static_call(out, out_lse):
+        fa.fa_fwd_ex(dtype=fa.FA_DTYPE_BF16, q=qd, k=kd, v=vd, o=out, lse=out_lse, seq_lens=sl, batch=1, heads=H, max_len=N,
+                     head_dim=D, scale=0.125, rope_cos=cd, rope_sin=sd, static_scratch=True)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        static_call(o, lse)                     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        static_call(o, lse)
+    for rep in range(3):
+        _, q, k, v = draw(9800 + rep, 1, H, N, D, dtype)
+        qd.copy_(to_dev(q, dtype)); kd.copy_(to_dev(k, dtype)); vd.copy_(to_dev(v, dtype))
+        o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_o, got_lse = o.clone(), lse.clone()
+        o2, lse2 = poison((1, H, N, D), dtype), torch.zeros_like(lse)
+        fa.fa_fwd_ex(dtype=fa.FA_DTYPE_BF16, q=qd, k=kd, v=vd, o=o2, lse=lse2, seq_lens=sl, batch=1, heads=H, max_len=N,
+                     head_dim=D, scale=0.125, rope_cos=cd, rope_sin=sd, scratch=lent, scratch_bytes=need)
+        torch.cuda.synchronize()
+        assert torch.equal(got_o, o2) and torch.equal(got_lse, lse2), f"replay {rep} differs from the eager call"
