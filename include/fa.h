@@ -192,8 +192,8 @@ typedef struct fa_params {
                                 head_dim 64 without a key bias; ignored otherwise) */
 #define FA_TUNE_BM_512 0x5u  /* 8 wavefronts x 64 query rows sharing one K/V stage (same restriction) */
 #define FA_TUNE_BM_MIXED 0x6u /* 256-row and 128-row workgroups in one launch, split on the device from
-                                 the sequence length (same restriction, and one sequence of at most
-                                 768 tiles of 128 rows over all heads; ignored otherwise) */
+                                 the sequence length (same restriction, and batch 1, heads <= 256;
+                                 ignored otherwise) */
 #define FA_TUNE_V_AUTO 0x00u
 #define FA_TUNE_V_LDS_TRANSPOSE 0x10u /* ds_read_b64_tr_b16 operand loads */
 #define FA_TUNE_V_SCALAR 0x20u        /* 16-bit LDS reads (slow reference path) */

@@ -9,6 +9,7 @@
 
 #include "fa.h"
 #include "fa_args.h"
+#include "fa_mix_map.h"
 
 namespace {
 
@@ -62,12 +63,12 @@ bool output_rows_disjoint(const int64_t st[3], int batch, int heads, int max_len
   return true;
 }
 
-// One sequence whose 128-row tiles number at most three per compute unit can take the
-// mixed-shape kernel (it splits them between 256-row and 128-row workgroups itself, from the
-// sequence length); heads <= 256 keeps the 128-row tiles left over by an odd tile count within
-// the 512 workgroup ids the launch reserves for them.
+// One sequence can take the mixed-shape kernel (it splits the rows between 256-row and 128-row
+// workgroups itself, from the sequence length); heads <= 256 keeps the 128-row workgroups left
+// over by an odd tile count within the ids the launch reserves for them.
 bool mixed_fits(const fa_params& p) {
-  return p.batch == 1 && p.heads <= 256 && (((int64_t)p.max_len + 127) / 128) * p.heads <= 768;
+  const int64_t tiles = ((int64_t)p.max_len + 127) / 128;
+  return p.batch == 1 && p.heads <= 256 && tiles * p.heads <= (1 << 20) && fa_mix_ids((int)tiles, p.heads) >= 0;
 }
 
 // Relative time of a global layer of head_dim 64 under a tile shape, from how its workgroups
@@ -107,7 +108,10 @@ int choose_bm(const fa_params& p) {
   const int64_t w256 = (((int64_t)p.max_len + 255) / 256) * bh;
   const int64_t w512 = (((int64_t)p.max_len + 511) / 512) * bh;
   if (w128 <= 512) return 128;                      // at most two 128-row workgroups per unit
-  if (w128 <= 768 && mixed_fits(p)) return 0;       // one 256-row and one 128-row workgroup per unit
+  // one sequence: pairs of one 256-row and one 128-row workgroup per unit (up to 768 tiles), or
+  // rounds of 256-row pairs with 128-row workgroups on what remains (beyond 1024; between the
+  // two a single round of the larger shapes does as well)
+  if ((w128 <= 768 || w128 > 1024) && mixed_fits(p)) return 0;
   const double c128 = shape_cost(w128, 3, 4, 1.08), c256 = shape_cost(w256, 2, 8, 1.0),
                c512 = shape_cost(w512, 1, 16, 0.98);
   if (c512 < c256 && c512 < c128 && w512 <= 256) return 512;   // 512 only where one round holds the call
@@ -290,6 +294,7 @@ int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool
   const int64_t per = ((int64_t)p->heads * n_qtiles + 7) / 8;
   if (8 * per * p->batch > 0x7FFFFFF0LL) return FA_ERR_BAD_SHAPE;
   a.xcd_per = (int32_t)per;
+  a.mix_ids_a = bm == 0 ? fa_mix_ids((int)n_qtiles, p->heads) : 0;
   const int v_path = t_v == FA_TUNE_V_SCALAR ? 1 : 0;
 
   const unsigned t_win = p->tuning & 0xF000u;

@@ -27,6 +27,7 @@ struct FaKernelArgs {
   int32_t total_tiles;  // batch * heads * n_qtiles
   int32_t map_xcd;  // nonzero: each XCD owns a contiguous eighth of every batch element's tiles
   int32_t xcd_per;  // ceil(heads * n_qtiles / 8)
+  int32_t mix_ids_a; // mixed-shape kernel: workgroup ids reserved for 256-row workgroups (fa_mix_map.h)
 };
 
 // Rotation of q and k ahead of a global layer (rows of both tensors rotated by position and
@@ -49,7 +50,7 @@ int fa_static_scratch(void** ptr);
 
 // Host-side launchers implemented in fa_kernels.hip.  Return hipError_t as int.
 // bm: query rows per workgroup: 32 (key-split kernel), 128, 256, 384 (12 wavefronts), 512 (8
-// wavefronts), or 0 = 256-row and 128-row workgroups mixed (one sequence of at most 768 tiles of 128 rows over all heads); v_path: 0 = LDS
+// wavefronts), or 0 = 256-row and 128-row workgroups mixed (one sequence, a.mix_ids_a set); v_path: 0 = LDS
 // transpose reads, 1 = 16-bit reads.
 // win_kernel: 0 = library's choice among the window kernels, 1 = never the two-phase kernel, 2 = the
 // two-phase kernel wherever it applies.

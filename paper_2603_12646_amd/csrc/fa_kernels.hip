@@ -58,6 +58,7 @@
 
 #include "fa.h"
 #include "fa_args.h"
+#include "fa_mix_map.h"
 
 namespace {
 
@@ -2109,30 +2110,17 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void fa_fwd_global_kernel
 
 // ======================================================================================
 // Mixed-shape global kernel (head_dim 64, ONE sequence): 256-row and 128-row workgroups in one
-// launch, for calls whose 128-row tiles number between two and three per compute unit (one
-// 8K-token sequence of 12 heads: 744 tiles on 256 units).  The 128-row shape alone runs such a
-// call at three wavefronts per SIMD with three times the K/V tile traffic of the 256-row
-// shape; the 256-row shape alone leaves units with 16 query blocks beside units with 8.
-// Here the tiles are dealt as PAIRS of one 256-row workgroup (two query blocks per wavefront)
-// and one 128-row workgroup, a pair per compute unit: three blocks per SIMD on two wavefronts.
-// (A 256-row workgroup must not be alone on its unit: a single wavefront per SIMD overlaps
-// its own matrix and vector work badly and runs at less than half the rate.)
-//
-// The split is made ON THE DEVICE from the sequence length n, which the host does not know:
-// with T = ceil(n / 128) tiles per head and U = T * heads tiles in all,
-//   U <= 512 or T < 2: no 256-row workgroups (at most two 128-row workgroups per unit anyway);
-//   otherwise: A = U / 3 workgroups of 256 rows, dealt to the heads as evenly as integers allow
-//             (head h gets floor(A (h+1) / heads) - floor(A h / heads) of them, covering its
-//             FIRST rows), and 128-row workgroups on the rows after them: U - 2 A of those.
-// The host launches 256 + 512 workgroup ids whenever ceil(max_len / 128) * heads <= 768 (so
-// U <= 768 whatever n is); ids [0, 256) are the 256-row range and come first, so that the
-// dispatcher spreads them over the compute units before the 128-row workgroups follow.
-// Within each range ids are dealt round-robin to the 8 XCDs and every XCD takes a contiguous
-// eighth of the range's (head, tile) list, as in the other kernels.  Ids without a tile
-// zero-fill the tiles that lie entirely in the padding (rows at or beyond 128 T), or exit.
+// launch.  A launch of 256-row workgroups alone ends, unless their number is a multiple of 512,
+// with a round in which units hold one workgroup (a single wavefront per SIMD overlaps its own
+// matrix and vector work badly and runs at less than half the rate) or none; the 128-row shape
+// alone moves twice the K/V tile traffic per flop.  Here full rounds of 256-row pairs are
+// followed by 128-row workgroups, or by pairs of one of each, on the rows that remain (one
+// 8K-token sequence of 12 heads: 248 pairs on 256 units; one 16K-token sequence: 512 + 512).
+// The split is made ON THE DEVICE from the sequence length, which the host does not know; the
+// id -> tile arithmetic and its rules are in fa_mix_map.h.  The host launches mix_ids_a +
+// kMixIdsB ids, enough for every length up to max_len.  Ids without a tile zero-fill the tiles
+// that lie entirely in the padding (rows at or beyond 128 T), or exit.
 // ======================================================================================
-constexpr int kMixIdsA = 256, kMixIdsB = 512;
-
 template <class T>
 __global__ __launch_bounds__(kThreads, 2) void fa_fwd_global_mixed_kernel(const FaKernelArgs a) {
   typedef GlobalLds<kD, 4> L;
@@ -2145,63 +2133,31 @@ __global__ __launch_bounds__(kThreads, 2) void fa_fwd_global_mixed_kernel(const 
     n = a.seq_lens[0];
     n = n < 0 ? 0 : (n > N ? N : n);
   }
-  const int tiles = (n + 127) >> 7, U = tiles * H;  // T and U of the comment above
-  const int a_tot = (U > 512 && tiles >= 2) ? U / 3 : 0;
-  const int b_tot = U - 2 * a_tot;
-  auto bnd = [&](int h) { return a_tot * h / H; };  // 256-row workgroups of heads 0 .. h-1
-  // Position of this id in its range's tile list, or, for an id that has no tile there, its
-  // index among the spare ids of the launch (spare >= 0).  With the XCD-aware order XCD x owns
-  // list entries [x per, x per + per), per = ceil(entries / 8), on ids x, x + 8, x + 16, ...
-  const int bid = (int)blockIdx.x;
-  const bool range_a = bid < kMixIdsA;
-  const int j = range_a ? bid : bid - kMixIdsA;
-  const int tot = range_a ? a_tot : b_tot, ids = range_a ? kMixIdsA : kMixIdsB;
-  const int per = (tot + 7) >> 3;
-  const int spare_a = a.map_xcd ? kMixIdsA - 8 * ((a_tot + 7) >> 3) : kMixIdsA - a_tot;
-  const int spare_b = a.map_xcd ? kMixIdsB - 8 * ((b_tot + 7) >> 3) : kMixIdsB - b_tot;
-  int t, spare = -1;
-  if (a.map_xcd) {
-    const int x = j & 7, p = j >> 3;
-    t = x * per + p;
-    if (p >= per) spare = x * (ids / 8 - per) + (p - per);
-    else if (t >= tot) return;    // at most seven ids per range: the rounding of per
-  } else {
-    t = j;
-    if (t >= tot) spare = t - tot;
-  }
+  const int tiles = (n + 127) >> 7;
+  const FaMixTile m = fa_mix_locate((int)blockIdx.x, a.map_xcd != 0, a.mix_ids_a, kMixIdsB, H, tiles);
   TileCoord tc;
   tc.b = 0;
   tc.n = n;
-  if (spare >= 0) {
-    // tiles tiles .. ceil(max_len / 128) - 1 of every head are padding only: o = 0, lse = -inf.
+  // (wavefront-uniform by construction; said explicitly so that the addresses derived from
+  // them stay in scalar registers)
+  tc.h = __builtin_amdgcn_readfirstlane(m.head);
+  tc.q0 = __builtin_amdgcn_readfirstlane(m.q0);
+  if (m.kind == 1) {
+    tc.qt = m.q0 >> 8;
+    global_body<T, kD, 2, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
+  } else if (m.kind == 2) {
+    tc.qt = m.q0 >> 7;
+    global_body<T, kD, 1, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
+  } else if (m.kind == 3) {
+    // tiles T .. ceil(max_len / 128) - 1 of every head are padding only: o = 0, lse = -inf.
     // The spare ids share them out in a strided loop (there are normally more ids than tiles).
     const int pad = ((N + 127) >> 7) - tiles;
-    const int spares = spare_a + spare_b;
-    for (int z = (range_a ? 0 : spare_a) + spare; z < pad * H; z += spares) {
+    for (int z = m.spare; z < pad * H; z += m.spares) {
       tc.h = z / pad;
       tc.qt = tiles + z % pad;
       tc.q0 = 128 * tc.qt;
       zero_fill<128, kD, kThreads>(a, tc, (uint16_t*)a.o + tc.h * a.os[1], a.lse ? a.lse + (int64_t)tc.h * N : nullptr);
     }
-    return;
-  }
-  if (range_a) {
-    int h = (int)((int64_t)t * H / a_tot);
-    if (bnd(h + 1) <= t) ++h;
-    tc.h = h;
-    tc.qt = t - bnd(h);
-    tc.q0 = 256 * tc.qt;
-    global_body<T, kD, 2, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
-  } else {
-    // 128-row tiles of heads 0 .. h-1: h * tiles - 2 bnd(h), increasing in h
-    auto pre = [&](int h) { return h * tiles - 2 * bnd(h); };
-    int h = (int)((int64_t)t * H / b_tot);
-    while (h > 0 && pre(h) > t) --h;
-    while (h + 1 < H && pre(h + 1) <= t) ++h;
-    tc.h = h;
-    tc.qt = t - pre(h);
-    tc.q0 = 256 * (bnd(h + 1) - bnd(h)) + 128 * tc.qt;
-    global_body<T, kD, 1, 4, false, false>(a, tc, lds_k, lds_v, lds_bias);
   }
 }
 
@@ -2241,7 +2197,7 @@ int launch(const FaKernelArgs& a, int bm, int v_path, int win_kernel, void* stre
   typedef void (*Kernel)(const FaKernelArgs);
   unsigned grid = (unsigned)a.total_tiles;
   if (a.map_xcd) grid = 8u * (unsigned)a.xcd_per * (unsigned)a.batch;
-  if (bm == 0) grid = kMixIdsA + kMixIdsB;
+  if (bm == 0) grid = a.mix_ids_a + kMixIdsB;
   const bool global = a.wl < 0 && a.wr < 0;
   // per-lane 32-bit byte offsets into a (batch, head) slice
   const bool slice_fits_32bit = (double)a.max_len * (double)(a.ks[2] > a.vs[2] ? a.ks[2] : a.vs[2]) * 2.0 < 4.0e9;

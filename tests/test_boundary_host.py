@@ -222,7 +222,8 @@ int main() {
   p.window_left = p.window_right = -1;
   EXPECT(fa_fwd_ex(&p) == 0 && launches == 1 && last_bm == 0);            // one 8K sequence: the mixed launch
   p.heads = 16; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 512);
-  p.heads = 24; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 256);
+  p.heads = 24; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 0 && last.mix_ids_a == 768);   // 1536 tiles: 768 of 256 rows
+  p.batch = 2; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 256 && last.mix_ids_a == 0); p.batch = 1;
   p.heads = 12; p.max_len = 512; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 32);
   p.batch = 32; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 128);
   p.batch = 1; p.max_len = 32768; p.window_left = 63; p.window_right = 64;
@@ -308,3 +309,92 @@ def test_host_boundary_under_address_and_undefined_sanitizers(tmp_path):
     r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
     assert r.returncode == 0, r.stdout + r.stderr
     assert r.stdout.startswith("ok ") and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
+
+
+MIX_MAP_DRIVER = r"""
+// Every workgroup id of the mixed-shape launch walked on the CPU: for each (heads, max_len, n,
+// id order) the 256-row and 128-row tiles handed out must cover rows [0, 128 T) of every head
+// exactly once and stay inside them, and the spare ids must be numbered 0 .. spares-1 once each.
+#include <cstdio>
+#include <vector>
+#include "fa_mix_map.h"
+
+static long cases = 0;
+
+static int check(int H, int max_len, int n, bool map_xcd) {
+  const int tmax = (max_len + 127) / 128, tiles = (n + 127) / 128;
+  const int ids_a = fa_mix_ids(tmax, H);
+  if (ids_a < 0 || ids_a % 8) { printf("ids_a %d for H %d tmax %d\n", ids_a, H, tmax); return 1; }
+  std::vector<int> cover((size_t)H * tiles, 0);
+  std::vector<int> spare_seen;
+  int spares = -1, n_a = 0, n_b = 0;
+  for (int bid = 0; bid < ids_a + kMixIdsB; ++bid) {
+    const FaMixTile m = fa_mix_locate(bid, map_xcd, ids_a, kMixIdsB, H, tiles);
+    if (m.kind == 0) continue;
+    if (m.kind == 3) {
+      if (spares < 0) { spares = m.spares; spare_seen.assign(spares, 0); }
+      if (m.spares != spares || m.spare < 0 || m.spare >= spares || spare_seen[m.spare]++) { printf("spare id %d\n", bid); return 1; }
+      continue;
+    }
+    const int rows = m.kind == 1 ? 256 : 128;
+    if (m.kind == 1 && bid >= ids_a) { printf("256-row tile on id %d of the 128-row range\n", bid); return 1; }
+    if (m.kind == 2 && bid < ids_a) { printf("128-row tile on id %d of the 256-row range\n", bid); return 1; }
+    if (m.head < 0 || m.head >= H || m.q0 < 0 || m.q0 % 128 || m.q0 + rows > 128 * tiles) {
+      printf("H %d max_len %d n %d xcd %d id %d: kind %d head %d q0 %d\n", H, max_len, n, (int)map_xcd, bid, m.kind, m.head, m.q0);
+      return 1;
+    }
+    for (int t = m.q0 / 128; t < (m.q0 + rows) / 128; ++t) ++cover[(size_t)m.head * tiles + t];
+    (m.kind == 1 ? n_a : n_b)++;
+  }
+  for (size_t i = 0; i < cover.size(); ++i)
+    if (cover[i] != 1) { printf("H %d max_len %d n %d xcd %d: head %zu tile %zu covered %d times\n", H, max_len, n, (int)map_xcd, i / tiles, i % tiles, cover[i]); return 1; }
+  if (spares >= 0) for (int s : spare_seen) if (s != 1) { printf("spare numbering\n"); return 1; }
+  if (tiles < tmax && spares <= 0) { printf("H %d max_len %d n %d: padding tiles but no spare id\n", H, max_len, n); return 1; }
+  if (n_a != fa_mix_a_total(tiles, H) || 2 * n_a + n_b != tiles * H) { printf("totals\n"); return 1; }
+  ++cases;
+  return 0;
+}
+
+int main() {
+  // the split itself: the documented regimes
+  if (fa_mix_a_total(64, 12) != 256 || fa_mix_a_total(128, 12) != 768 || fa_mix_a_total(192, 12) != 1024 || fa_mix_a_total(256, 12) != 1536 ||
+      fa_mix_a_total(32, 12) != 0 || fa_mix_a_total(1, 1000) != 0 || fa_mix_a_total(96, 12) != 512 ||
+      fa_mix_a_total(3, 400) != 400) { printf("split rule\n"); return 1; }
+  const int heads[] = {1, 2, 3, 5, 7, 8, 12, 13, 16, 24, 32, 64, 100, 255, 256};
+  const int lens[] = {1, 127, 128, 129, 300, 1000, 2048, 4097, 7900, 8192, 10000, 12288, 16384, 20000, 24576, 28672, 32768, 40000, 65536};
+  for (int H : heads)
+    for (int N : lens)
+      for (int xcd = 0; xcd < 2; ++xcd) {
+        // n = N, a few lengths inside every regime below it, and the empty sequence
+        const int ns[] = {N, N - 1, N - 127, N - 128, N / 2, N / 3, (int)(N * 0.8), 129, 1, 0};
+        for (int n : ns) {
+          if (n < 0) continue;
+          if (check(H, N, n, xcd != 0)) return 1;
+        }
+      }
+  // every length of one 12-head and one 5-head call
+  for (int n = 0; n <= 16384; n += 97) if (check(12, 16384, n, true) || check(5, 16384, n, false)) return 1;
+  printf("ok %ld cases\n", cases);
+  return 0;
+}
+"""
+
+
+def test_mixed_launch_covers_every_tile_exactly_once(tmp_path):
+    """The id -> tile arithmetic the mixed-shape kernel evaluates on the device (fa_mix_map.h),
+    compiled for the host and walked id by id under the sanitizers."""
+    import shutil
+    import subprocess
+
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    src = tmp_path / "mixmap.cpp"
+    src.write_text(MIX_MAP_DRIVER)
+    exe = tmp_path / "mixmap"
+    csrc = ROOT / "paper_2603_12646_amd" / "csrc"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-I", str(csrc), str(src), "-o", str(exe)], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.startswith("ok ") and "runtime error" not in r.stderr

@@ -284,7 +284,11 @@ def test_key_split_kernel_ring_and_ragged_ends(dtype, B, H, N, lens):
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 @pytest.mark.parametrize("H,N,n", [(12, 8192, 7900), (12, 8192, 8192), (12, 8192, 5500), (12, 8192, 5376),
                                    (12, 8192, 3000), (12, 8192, 0), (5, 16384, 16001), (7, 8192, 8191),
-                                   (48, 2048, 1999), (96, 1024, 1024), (200, 384, 383)])
+                                   (48, 2048, 1999), (96, 1024, 1024), (200, 384, 383),
+                                   # beyond 1024 tiles: rounds of 256-row pairs, then 128-row workgroups / pairs / 256-row
+                                   (12, 16384, 16384), (12, 16384, 12288), (12, 16384, 14000), (12, 16384, 10100),
+                                   (16, 16384, 16384), (24, 8192, 6000), (20, 8192, 8000), (13, 12288, 11000),
+                                   (255, 1024, 1000), (3, 32768, 30000), (12, 20000, 19999)])
 def test_mixed_shape_launch_covers_every_row(dtype, H, N, n):
     """One sequence, 256-row and 128-row workgroups in one launch, split on the device from the
     length: every row must come out exactly as the 128-row kernel computes it (the per-row
