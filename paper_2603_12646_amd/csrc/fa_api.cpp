@@ -90,7 +90,7 @@ double shape_cost(int64_t workgroups, int slots, int blocks, double rel) {
   return rounds * slots * blocks * rel;
 }
 
-int choose_bm(const fa_params& p) {
+int choose_bm(const fa_params& p, bool allow_mixed) {
   // Query rows per workgroup (0 = the mixed-shape kernel).  256 (two 32-row blocks per
   // wavefront) halves LDS and L2 traffic per flop and 512 (eight wavefronts on one K/V stage)
   // halves the L2 traffic again, but the larger the tile the coarser the load balance over
@@ -111,7 +111,7 @@ int choose_bm(const fa_params& p) {
   // one sequence: pairs of one 256-row and one 128-row workgroup per unit (up to 768 tiles), or
   // rounds of 256-row pairs with 128-row workgroups on what remains (beyond 1024; between the
   // two a single round of the larger shapes does as well)
-  if ((w128 <= 768 || w128 > 1024) && mixed_fits(p)) return 0;
+  if (allow_mixed && (w128 <= 768 || w128 > 1024) && mixed_fits(p)) return 0;
   const double c128 = shape_cost(w128, 3, 4, 1.08), c256 = shape_cost(w256, 2, 8, 1.0),
                c512 = shape_cost(w512, 1, 16, 0.98);
   if (c512 < c256 && c512 < c128 && w512 <= 256) return 512;   // 512 only where one round holds the call
@@ -224,13 +224,12 @@ int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool
     // 384 (12 wavefronts x 32 rows), 512 (8 wavefronts x 64 rows) and the mixed launch exist for
     // global layers without a key bias on the transpose-read path only
     const bool plain = !windowed && !p->key_bias && !p->rope_cos && t_v != FA_TUNE_V_SCALAR;
-    bm = choose_bm(*p);
+    bm = choose_bm(*p, plain);
     if (t_bm == FA_TUNE_BM_128) bm = 128;
     if (t_bm == FA_TUNE_BM_256) bm = 256;
     if (t_bm == FA_TUNE_BM_384 && plain) bm = 384;
     if (t_bm == FA_TUNE_BM_512 && plain) bm = 512;
     if (t_bm == FA_TUNE_BM_MIXED && plain && mixed_fits(*p)) bm = 0;
-    if (!plain && bm == 0) bm = 128;
     if (!plain && bm == 512) bm = 256;
   } else if (p->head_dim == 128 && !windowed && !p->key_bias && !p->rope_cos && t_v != FA_TUNE_V_SCALAR) {
     // head_dim 128 global layers: 128 rows on four wavefronts (two workgroups per unit), or 256
@@ -242,12 +241,12 @@ int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool
     if (t_bm == FA_TUNE_BM_128) bm = 128;
     if (t_bm == FA_TUNE_BM_256) bm = 256;
   } else if (p->head_dim == 32 && !windowed && !p->key_bias && t_v != FA_TUNE_V_SCALAR) {
-    // head_dim 32 global layers: the pipelined kernel in its 128- and 256-row shapes
-    bm = choose_bm(*p);
+    // head_dim 32 global layers: the pipelined kernel in its 128- and 256-row shapes, chosen by
+    // the same fill model (it matches a sweep of 1K-32K tokens x 8-24 heads to within 1 %)
+    bm = choose_bm(*p, false);
+    if (bm == 512) bm = 256;
     if (t_bm == FA_TUNE_BM_128) bm = 128;
     if (t_bm == FA_TUNE_BM_256) bm = 256;
-    if (bm == 0) bm = 128;
-    if (bm == 512) bm = 256;
   }
   // Key-split kernel (32 query rows per workgroup, the wavefronts split the keys): global
   // layers of head_dim 64 without a bias whose 32-row blocks number at most one per compute

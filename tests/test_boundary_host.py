@@ -235,7 +235,11 @@ int main() {
       EXPECT(fa_fwd_ex(&p) == 0);
       EXPECT(last.total_tiles > 0 && last.n_qtiles > 0 && last.xcd_per > 0);
     }
-  p.tuning = 0; p.head_dim = 64;
+  p.tuning = 0;
+  // head_dim 32 never takes the mixed launch: 256 rows where the fill model says so
+  p.head_dim = 32; p.heads = 24; p.max_len = 8192; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 256);
+  p.heads = 12; EXPECT(fa_fwd_ex(&p) == 0 && last_bm == 128);
+  p.head_dim = 64; p.max_len = 32768;
   // strides: [batch, len, heads, dim] passes, interleaved output rows do not
   const int64_t bshd[3] = {(int64_t)32768 * 12 * 64, 64, 12 * 64};
   std::memcpy(p.q_strides, bshd, sizeof bshd); std::memcpy(p.o_strides, bshd, sizeof bshd);
@@ -254,6 +258,8 @@ int main() {
   p.batch = 1; p.heads = 12; p.max_len = 8192; p.head_dim = 64; p.scale = 0.125f; p.window_left = p.window_right = -1;
   p.rope_cos = p.rope_sin = table;
   EXPECT(fa_fwd_ex(&p) == 0 && rotations == 0 && last.rope_cos == table && last_bm != 0 && last.q == P);
+  p.max_len = 32768; EXPECT(fa_fwd_ex(&p) == 0 && rotations == 0 && last_bm == 256);       // rotation in the call: never the mixed launch
+  p.max_len = 8192;
   p.scratch = lent; p.scratch_bytes = fa_rope_scratch_bytes(1, 12, 8192, 64) - 1;
   EXPECT(fa_fwd_ex(&p) == 0 && rotations == 0 && last.rope_cos == table);                    // too small: ignored
   p.scratch_bytes += 1;
