@@ -215,8 +215,7 @@ int fwd_ex_impl(const fa_params* p_in, void* scratch, size_t scratch_bytes, bool
     }
   }
 
-  // head_dim 128 runs 128-row kernels only (the tile-size hint is ignored there), and so does a key
-  // bias unless it can ride on the pipelined global kernel
+  // a key bias runs 128-row kernels only unless it can ride on the pipelined global kernel
   const bool windowed = p->window_left >= 0 || p->window_right >= 0;
   const bool bias_on_masked_kernel = p->key_bias && (windowed || p->scale == 0.0f || (p->tuning & 0xF0u) == FA_TUNE_V_SCALAR);
   int bm = 128;
