@@ -308,6 +308,29 @@ def test_mixed_shape_launch_covers_every_row(dtype, H, N, n):
             assert np.abs(lse2[0, h, rows] - lse_ref).max() <= LSE_TOL
 
 
+@pytest.mark.parametrize("H,N,n", [(12, 8192, 7000), (10, 16384, 12345)])
+def test_mixed_shape_launch_reads_packed_qkv_and_writes_bshd(H, N, n):
+    """The mixed launch on [len, 3, heads, dim] packed inputs and a [len, heads, dim] output: bit
+    for bit what the 128-row kernel produces from dense copies, padded rows (whole tiles of them
+    are filled by the launch's spare workgroup ids) included."""
+    D, dtype = 64, "fp16"
+    _, q, k, v = draw(4300 + H, 1, H, N, D, dtype)
+    o_ref, lse_ref = run_simple(q, k, v, [n], dtype, 0.125, tuning=fa.FA_TUNE_BM_128)
+    packed = np.stack([q, k, v], axis=0).transpose(1, 3, 0, 2, 4).copy()  # 1, N, 3, H, D
+    dev = to_dev(packed, dtype)
+    o = poison((1, N, H, D), dtype)
+    lse = torch.full((1, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    sl = torch.tensor([n], dtype=torch.int32).cuda()
+    st = (N * 3 * H * D, D, 3 * H * D)
+    fa.fa_fwd_ex(dtype=FA_DT[dtype], q=dev[:, :, 0].data_ptr(), k=dev[:, :, 1].data_ptr(), v=dev[:, :, 2].data_ptr(),
+                 o=o, lse=lse, seq_lens=sl, batch=1, heads=H, max_len=N, scale=0.125, q_strides=st, k_strides=st,
+                 v_strides=st, o_strides=(N * H * D, D, H * D), tuning=fa.FA_TUNE_BM_MIXED)
+    torch.cuda.synchronize()
+    assert np.array_equal(o.double().cpu().numpy().transpose(0, 2, 1, 3), o_ref)
+    assert np.array_equal(lse.double().cpu().numpy(), lse_ref)
+    assert np.all(o_ref[0, :, n:] == 0) and np.all(np.isneginf(lse_ref[0, :, n:]))
+
+
 def test_key_split_merge_with_far_apart_maxima():
     """Each wavefront's share of the keys has its own score level (key block j scores about
     6 * (j % 4) higher): the merge has to scale three of the four partial results far down."""
