@@ -1353,15 +1353,29 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
 
   // ---- phase 2: request V into the same region; softmax meanwhile
   request_blocks(vp, a.vs[2], false);
+  // The paper's window (63 left, 64 right) away from the ends of the sequence: the wavefront's 32
+  // queries see five blocks, the middle three completely, and of the outer two query t (0..31)
+  // sees keys t+1..31 of the first and keys 0..t of the last: between them exactly one block's
+  // worth of keys per query.  The last block's scores are merged into the first's (element by
+  // element, the one the query sees), the merged block takes the unmasked path like the middle
+  // three, and its probabilities are dealt back to the two blocks for the P.V products.  A
+  // masked block costs three times the vector instructions of an unmasked one.
+  const bool merged_ends = a.wl == 63 && a.wr == 64 && qw0 >= 64 && qw0 + 96 <= n;   // wavefront-uniform; implies cnt == 5
+  if (merged_ends) {
+    // accumulator element r is key offset 8 (r / 4) + 4 hh + r % 4 of its block
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[0][r] = 8 * (r >> 2) + (r & 3) <= l32 - 4 * hh ? sc[4][r] : sc[0][r];
+  }
+  const int cnt2 = merged_ends ? 4 : cnt;   // blocks that go through the softmax
   uint32_t vis[kTwoPhaseBlocks];
   float t0 = -INFINITY;
 #pragma unroll
   for (int i = 0; i < kTwoPhaseBlocks; ++i) {
     vis[i] = 0;
-    if (i < cnt) {
+    if (i < cnt2) {
       const int kb0 = (fb + i) * 32;
       // blocks every valid query of the wavefront sees completely need no mask work
-      const bool interior = kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr;
+      const bool interior = (kb0 + 32 <= n && kb0 >= qw_last - a.wl && kb0 + 31 <= qw0 + a.wr) || (i == 0 && merged_ends);
       if (interior) {
         vis[i] = 0xFFFFu;
 #pragma unroll
@@ -1381,7 +1395,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
   typename T::v8 pr[kTwoPhaseBlocks][2];
 #pragma unroll
   for (int i = 0; i < kTwoPhaseBlocks; ++i) {
-    if (i < cnt) {
+    if (i < cnt2) {
       uint32_t pk[8];
       float blk;
       if (vis[i] == 0xFFFFu) prob_block<T, false>(sc[i], c, st.mc[0], vis[i], pk, blk);
@@ -1391,6 +1405,24 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
       pr[i][1] = as_v8<T>(make_uint4(pk[4], pk[5], pk[6], pk[7]));
     } else {
       pr[i][0] = pr[i][1] = as_v8<T>(make_uint4(0, 0, 0, 0));
+    }
+  }
+  if (merged_ends) {
+    // the merged block's probabilities back to their blocks: pair r holds key offsets k0, k0 + 1
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const uint4 u = __builtin_bit_cast(uint4, pr[0][h2]);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+      uint32_t first[4], last[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int r = 4 * h2 + x, k0 = 8 * (r >> 1) + 2 * (r & 1), thr = l32 - 4 * hh;
+        const uint32_t m = (k0 <= thr ? 0x0000FFFFu : 0u) | (k0 + 1 <= thr ? 0xFFFF0000u : 0u);
+        last[x] = w[x] & m;
+        first[x] = w[x] & ~m;
+      }
+      pr[0][h2] = as_v8<T>(make_uint4(first[0], first[1], first[2], first[3]));
+      pr[4][h2] = as_v8<T>(make_uint4(last[0], last[1], last[2], last[3]));
     }
   }
 
