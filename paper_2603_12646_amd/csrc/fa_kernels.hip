@@ -312,6 +312,18 @@ __device__ __forceinline__ void rescale_rows(RowState<NQB, D>& st, int qb, bool 
     for (int r = 0; r < 16; ++r) st.oacc[qb][db][r] *= alpha;
 }
 
+// Selection by bit r of a visibility word without a compare: the bit, sign-extended, is an
+// all-ones or all-zeros word (one v_bfe_i32), and one more bitwise instruction keeps the value or
+// replaces it (a test, a compare and a select would be three).
+__device__ __forceinline__ uint32_t bit_to_word(uint32_t vis, int r) { return (uint32_t)__builtin_amdgcn_sbfe((int)vis, r, 1); }
+__device__ __forceinline__ float keep_or_zero(float x, uint32_t vis, int r) {
+  return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, x) & bit_to_word(vis, r));
+}
+__device__ __forceinline__ float keep_or_neg_inf(float x, uint32_t vis, int r) {
+  const uint32_t m = bit_to_word(vis, r);
+  return __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, x) & m) | (0xFF800000u & ~m));
+}
+
 // Probabilities of one 32 x 32 block against the row's current reference, rounded and
 // packed as the B operand of the P.V product, plus the lane's share of their row sum.
 // fp16: the sum is taken over the ROUNDED probabilities (the numbers the matrix product
@@ -328,8 +340,8 @@ __device__ __forceinline__ void prob_block(const floatx16& sv, float c, float mc
     float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r], c, nmc));
     float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * r + 1], c, nmc));
     if (MASKED) {
-      e0 = (vis >> (2 * r) & 1) ? e0 : 0.f;
-      e1 = (vis >> (2 * r + 1) & 1) ? e1 : 0.f;
+      e0 = keep_or_zero(e0, vis, 2 * r);
+      e1 = keep_or_zero(e1, vis, 2 * r + 1);
     }
     pk[r] = T::pack2(e0, e1);
     if (!T::kSumRounded) {
@@ -407,15 +419,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
   uint32_t pk[NQB][8];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    uint32_t vis = 0xFFFFu;
-    if (MASKED) {
-      vis = 0;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int jg = kb0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-        vis |= (jg >= jlo[qb] && jg <= jhi[qb]) ? (1u << r) : 0u;
-      }
-    }
+    const uint32_t vis = MASKED ? visible_bits(kb0, hh, jlo[qb], jhi[qb]) : 0xFFFFu;
     float p[16];
     float ls;  // read after a possible rescale of the row state
     if (bias2) {
@@ -432,7 +436,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
       float tmax = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        if (MASKED && !(vis >> r & 1)) t[r] = -INFINITY;
+        if (MASKED) t[r] = keep_or_neg_inf(t[r], vis, r);
         tmax = fmaxf(tmax, t[r]);
       }
       tmax = max_xor32(tmax);
@@ -443,7 +447,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float e = __builtin_amdgcn_exp2f(t[r] - mcq);
-        if (MASKED) e = (vis >> r & 1) ? e : 0.f;
+        if (MASKED) e = keep_or_zero(e, vis, r);
         p[r] = e;
         ls += e;
       }
@@ -451,7 +455,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
       float tmax = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float sv = (!MASKED || (vis >> r & 1)) ? sacc[qb][r] : -INFINITY;
+        const float sv = MASKED ? keep_or_neg_inf(sacc[qb][r], vis, r) : sacc[qb][r];
         tmax = fmaxf(tmax, sv);
       }
       tmax = max_xor32(tmax);
@@ -462,7 +466,7 @@ __device__ __forceinline__ void simple_block(RowState<NQB, D>& st, const typenam
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float e = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][r], c, nmc));
-        if (MASKED) e = (vis >> r & 1) ? e : 0.f;
+        if (MASKED) e = keep_or_zero(e, vis, r);
         p[r] = e;
         ls += e;
       }
@@ -725,7 +729,7 @@ __device__ __forceinline__ void resident_unit(RowState<1>& st, const typename T:
   if (EDGE && __any(alive && st.m_ref[0] == -INFINITY)) {
     float t0 = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, keep_or_neg_inf(s_cur[r], vis, r));
     const float tmax = max_xor32(t0);
     if (st.m_ref[0] == -INFINITY) {
       st.m_ref[0] = tmax;
@@ -741,7 +745,7 @@ __device__ __forceinline__ void resident_unit(RowState<1>& st, const typename T:
     const bool row_trig = sum_xor32(trig ? 1.f : 0.f) > 0.f;
     float t0 = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? s_cur[r] : -INFINITY);
+    for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, keep_or_neg_inf(s_cur[r], vis, r));
     const float tmax = max_xor32(t0);
     rescale_rows(st, 0, row_trig, tmax, c);
     if (EDGE) prob_block<T, true>(s_cur, c, st.mc[0], vis, pk, blk);
@@ -1383,7 +1387,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
       } else {
         vis[i] = visible_bits(kb0, hh, jlo, jhi);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis[i] >> r & 1) ? sc[i][r] : -INFINITY);
+        for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, keep_or_neg_inf(sc[i][r], vis[i], r));
       }
     }
   }
@@ -1584,7 +1588,7 @@ __global__ __launch_bounds__(kThreads, 1) void fa_fwd_keysplit_kernel(const FaKe
       const uint32_t vis = kb0 + 32 <= n ? 0xFFFFu : visible_bits(kb0, hh, 0, n - 1);
       float t0 = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, (vis >> r & 1) ? sA[r] : -INFINITY);
+      for (int r = 0; r < 16; ++r) t0 = fmaxf(t0, keep_or_neg_inf(sA[r], vis, r));
       const float tmax = max_xor32(t0);
       st.m_ref[0] = tmax;
       st.mc[0] = tmax == -INFINITY ? 0.f : tmax * a.c;
