@@ -1264,40 +1264,56 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 2 : 4) void fa_fwd_window_twop
 
   // A direct load moves 1 KB = RPL rows of a block (lane L: row L / CH, chunk position L % CH of
   // the load), so a block is LPB loads; the loads of all blocks, numbered block * LPB + part,
-  // are dealt round-robin to the four wavefronts.  A lane's row is clamped to the last row of
-  // the tensor (rows >= n are masked or zeroed below), so its global offset is a per-lane
-  // 32-bit byte offset from the slice.
+  // are dealt round-robin to the four wavefronts: wavefront w issues loads w, w + 4, w + 8, ...
+  //   head_dim 64 (LPB 4): load x of the wavefront is block x, part w;
+  //   head_dim 128 (LPB 8): block x / 2, part w + 4 (x % 2);
+  //   head_dim 32 (LPB 2): block 2 x + w / 2, part w % 2.
+  // So a wavefront has NPART (1 or 2) distinct parts, whose per-lane offsets are computed once,
+  // and its blocks advance by a fixed step: the scalar base moves by a 64-bit add per block.
+  // A lane's row is clamped to the last row of the tensor where the tile reaches past it (rows
+  // >= n are masked or zeroed below); its global offset is then a per-lane 32-bit byte offset
+  // from the slice.
   constexpr int CH = D / 8, RPL = 64 / CH, LPB = 32 / RPL;   // D = 32: 4, 16, 2;  64: 8, 8, 4;  128: 16, 4, 8
   constexpr int kLoadsPerWave = kResBlocks * LPB / kWaves;
+  constexpr int NPART = LPB > kWaves ? LPB / kWaves : 1;
+  constexpr int BSTEP = LPB < kWaves ? kWaves / LPB : 1;     // blocks between consecutive loads of one part
+  const int blk0 = LPB < kWaves ? wave / LPB : 0;            // the wavefront's first block
   const bool all_rows_exist = b_hi_ld * 32 <= N;   // workgroup-uniform
   auto request_blocks = [&](const uint16_t* base, int64_t row_elems, bool is_k) {
     const uint32_t row_bytes = 2u * (uint32_t)row_elems;
+    int row_of[NPART];            // row within a block that this lane fetches, per part
+    uint32_t chunk_bytes[NPART];  // byte offset of its (swizzled) 16-byte chunk within the row
+    uint32_t lds_part[NPART];     // element offset of the part within a block's LDS slot
+#pragma unroll
+    for (int pi = 0; pi < NPART; ++pi) {
+      const int part = LPB >= kWaves ? wave + kWaves * pi : wave % LPB;
+      row_of[pi] = part * RPL + lane / CH;
+      const int swz = is_k ? k_swz_d<D>(row_of[pi]) : v_swz_d<D>(row_of[pi]);
+      chunk_bytes[pi] = 2u * (uint32_t)(((lane % CH) ^ swz) * 8);
+      lds_part[pi] = (uint32_t)(part * RPL * D);
+    }
     if (all_rows_exist) {
-      // no clamp needed: a load's per-lane offset depends on its part only (LPB / kWaves or one
-      // distinct value per wavefront), the block advances the scalar base
-      const uint16_t* blk_base = base + (int64_t)b_lo * 32 * row_elems;
+      uint32_t lane_off[NPART];
+#pragma unroll
+      for (int pi = 0; pi < NPART; ++pi) lane_off[pi] = (uint32_t)row_of[pi] * row_bytes + chunk_bytes[pi];
+      const int64_t blk_elems = 32 * row_elems;
+      const uint16_t* g = base + (int64_t)(b_lo + blk0) * blk_elems;
 #pragma unroll
       for (int x = 0; x < kLoadsPerWave; ++x) {
-        const int j = wave + kWaves * x;          // wavefront-uniform
-        const int i = j / LPB, part = j % LPB;
-        if (b_lo + i < b_hi_ld) {
-          const int r = part * RPL + lane / CH;   // row within the block
-          const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
-          load16_to_lds(blk_base + (int64_t)i * 32 * row_elems, (uint32_t)r * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8),
-                        &lds[i * kBlk + part * RPL * D]);
-        }
+        const int pi = x % NPART;
+        const int i = blk0 + (x / NPART) * BSTEP;   // wavefront-uniform
+        if (b_lo + i < b_hi_ld) load16_to_lds(g, lane_off[pi], &lds[i * kBlk + lds_part[pi]]);
+        if (pi == NPART - 1) g += BSTEP * blk_elems;
       }
     } else {
 #pragma unroll
       for (int x = 0; x < kLoadsPerWave; ++x) {
-        const int j = wave + kWaves * x;
-        const int i = j / LPB, part = j % LPB;
+        const int pi = x % NPART;
+        const int i = blk0 + (x / NPART) * BSTEP;
         if (b_lo + i < b_hi_ld) {
-          const int r = part * RPL + lane / CH;
-          const int swz = is_k ? k_swz_d<D>(r) : v_swz_d<D>(r);
-          const int jg = (b_lo + i) * 32 + r;
+          const int jg = (b_lo + i) * 32 + row_of[pi];
           const uint32_t jc = (uint32_t)(jg < N ? jg : N - 1);
-          load16_to_lds(base, jc * row_bytes + 2u * (uint32_t)(((lane % CH) ^ swz) * 8), &lds[i * kBlk + part * RPL * D]);
+          load16_to_lds(base, jc * row_bytes + chunk_bytes[pi], &lds[i * kBlk + lds_part[pi]]);
         }
       }
     }
